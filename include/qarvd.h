@@ -1,0 +1,177 @@
+/*
+ * qarvd.h - C ABI of the MI355X (gfx950) dual-scale W8A8 linear layer of Q-ARVD.
+ *
+ * Three operations, split as the paper's deployment splits them (appendix
+ * "Quantization Kernels and Extra Cost Analysis": the outlier/normal channel split is
+ * done offline, an activation-quantization kernel and an INT8-GEMM-plus-dequantization
+ * kernel run online):
+ *
+ *   qarvd_quantize_weight   offline: outlier detection, channel permutation, dual scales, INT8 weights
+ *   qarvd_quant_act         online:  gather-permute + per-token dynamic symmetric INT8
+ *   qarvd_w8a8_dual_gemm    online:  INT8xINT8->INT32 on MFMA, two accumulators, fp32 dequant + bias
+ *
+ * Conventions
+ *   - Every pointer is DEVICE memory unless its comment says "host".  The caller owns every
+ *     buffer; the library allocates nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *   - W is fp32 [N,K] row-major: N = d_out rows, K = d_in input channels.  X is [M,K] row-major
+ *     (tokens x channels).  Y is [M,N] row-major.  Leading dimensions are in ELEMENTS.
+ *   - Functions return a qarvd_status and never abort or throw.  Arguments are validated on
+ *     the host before anything is launched; on error nothing has been written.
+ *
+ * Packed K axis (the layout both INT8 operands share)
+ *   Position p of a packed row holds input channel perm[p].  With K_o outlier channels:
+ *
+ *       [ outlier block: K_o bytes | zeros up to a multiple of 32 | normal block: K-K_o bytes | zeros ]
+ *         ^0                                                       ^qarvd_packed_normal_offset(K_o)
+ *
+ *   and the whole row extent qarvd_packed_k(K, K_o) is a multiple of 128.  Both producers write
+ *   the zero padding themselves; zeros add nothing to either INT32 sum.  A row stride (ldxq,
+ *   ldwq) may be any multiple of 16 that is >= qarvd_packed_k(K, K_o); bytes past the packed
+ *   extent are neither read nor written.  When K is a multiple of 128 and K_o a multiple of 32
+ *   (every layer of the DiT workloads) there is no padding at all.
+ */
+#ifndef QARVD_H
+#define QARVD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QARVD_OK = 0,
+    QARVD_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, K_o outside [0,K], ld too small ... */
+    QARVD_ERR_UNSUPPORTED = -2, /* misaligned pointer / stride, unknown dtype, size beyond a kernel limit */
+    QARVD_ERR_WORKSPACE = -3,   /* workspace missing or smaller than the query says */
+    QARVD_ERR_HIP = -4          /* a HIP call or launch failed */
+} qarvd_status;
+
+typedef enum { QARVD_F32 = 0, QARVD_BF16 = 1 } qarvd_dtype;
+
+/* K above this would let an INT32 accumulator overflow (K * 127^2 must stay below 2^31). */
+#define QARVD_MAX_K 133143
+
+/*
+ * Detector parameters (Sec. 3.2, Eq. (new_threshold): tau = 3.5, alpha = 1.2; Fig. "outlier
+ * patterns" caption: the outlier count is aligned to a multiple of 32).
+ *   forced_mask  HOST pointer to K bytes (0/1) or NULL.  Non-NULL: the outlier set is exactly
+ *                the mask; detection and alignment are skipped (used for the all-outlier and
+ *                arbitrary-split checks).
+ */
+typedef struct {
+    double tau;
+    double alpha;
+    int32_t align;
+    const uint8_t *forced_mask;
+} qarvd_detect_cfg;
+
+/* Fills *cfg with the paper's defaults {3.5, 1.2, 32, NULL}. */
+void qarvd_default_detect_cfg(qarvd_detect_cfg *cfg);
+
+/* Human-readable name of a status code (static storage). */
+const char *qarvd_status_string(qarvd_status s);
+
+/* Offset of the normal block inside a packed row: K_o rounded up to a multiple of 32. */
+int32_t qarvd_packed_normal_offset(int32_t K_o);
+
+/*
+ * Extent in bytes of a packed row, a multiple of 128.  K_o < 0 returns the largest extent any
+ * K_o in [0,K] can need, for allocating before the split is known.  Returns 0 on bad arguments.
+ */
+int32_t qarvd_packed_k(int32_t K, int32_t K_o);
+
+/* Bytes of device workspace qarvd_quantize_weight needs for an [N,K] layer. */
+size_t qarvd_quantize_weight_workspace(int32_t N, int32_t K);
+
+/*
+ * OFFLINE weight step (Sec. 3.2; Sec. 2.2 Eq. (quantization); Sec. 4.1 per-channel weights).
+ *   1. v[k] = (float) sqrt( sum_j (double)W[j,k]^2 ), rows added in ascending j      (L2 norm vector v)
+ *   2. med = median(v), MAD = median(|v - med|)  (even K: mean of the two middle values) Eq. (mad)
+ *   3. channel k is flagged iff v[k] > max(med + tau/0.6745*MAD, alpha*med), in fp64     Eq. (new_threshold)
+ *   4. no flagged channel: K_o = 0 and the layer stays single-scale.  Otherwise K_o is the
+ *      flagged count rounded UP to a multiple of `align` (capped at K); the added channels are
+ *      the unflagged ones with the largest norm (ties: smaller index)                    Fig. caption
+ *   5. perm = [outlier channels ascending | normal channels ascending]                   Eq. (dual_scale)
+ *   6. per output row j and per block: s = max|W[j, block]| / 127 (fp32 division),
+ *      Wq = clip(rint(W / s), -127, 127) (round-half-even), s == 0 -> 0                  Eq. (quantization)
+ *
+ *   W          in   f32 [N, ldw]
+ *   cfg        in   host; NULL = defaults
+ *   Wq         out  i8  [N, ldwq] packed (see above); ldwq >= qarvd_packed_k(K, -1), multiple of 16
+ *   s_normal   out  f32 [N]     s_outlier  out f32 [N]  (0 for an empty block)
+ *   perm       out  i32 [K]     gather index: packed position p reads channel perm[p]
+ *   K_o_host   out  HOST int32
+ *   v_out      out  f32 [K] or NULL (the norm vector)
+ *   workspace       device, >= qarvd_quantize_weight_workspace(N, K) bytes, 256-byte aligned
+ * Synchronises `stream` before returning (K_o is read back).
+ */
+qarvd_status qarvd_quantize_weight(const float *W, int32_t N, int32_t K, int64_t ldw,
+                                   const qarvd_detect_cfg *cfg, int8_t *Wq, int64_t ldwq,
+                                   float *s_normal, float *s_outlier, int32_t *perm,
+                                   int32_t *K_o_host, float *v_out, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+/*
+ * ONLINE activation quantization (appendix, kernel (i) plus the online permutation; Sec. 2.2
+ * Eq. (quantization) with per-token dynamic symmetric scale):
+ *     a_m = max_k |X[m,k]| over all K channels;  s_x[m] = a_m / 127 (fp32 division)
+ *     Xq[m, pos(p)] = clip(rint(X[m, perm[p]] / s_x[m]), -127, 127);  s_x[m] == 0 -> 0
+ *   X     in   [M, ldx] of `xdt` (QARVD_F32 or QARVD_BF16; bf16 is widened exactly first)
+ *   perm  in   i32 [K] or NULL (identity; K_o must then be 0)
+ *   Xq    out  i8 [M, ldxq] packed for (K, K_o);  s_x out f32 [M]
+ * Fully asynchronous on `stream`.  X must be 16-byte aligned with ldx*sizeof(elem) % 16 == 0.
+ */
+qarvd_status qarvd_quant_act(const void *X, qarvd_dtype xdt, int32_t M, int32_t K, int64_t ldx,
+                             const int32_t *perm, int32_t K_o, int8_t *Xq, int64_t ldxq,
+                             float *s_x, void *stream);
+
+/*
+ * Static-scale variant (Sec. 4.1 "per-tensor static quantization for activations"): the scale
+ * is an input, there is no absmax pass, and the clip to [-127,127] can fire.
+ */
+qarvd_status qarvd_quant_act_static(const void *X, qarvd_dtype xdt, int32_t M, int32_t K,
+                                    int64_t ldx, const int32_t *perm, int32_t K_o, float scale,
+                                    int8_t *Xq, int64_t ldxq, void *stream);
+
+/*
+ * ONLINE GEMM + de-quantization (appendix, kernel (ii); Eq. (dual_scale)):
+ *     acc_o[m,j] = sum over the outlier block of Xq[m,p]*Wq[j,p]     (INT32, exact)
+ *     acc_n[m,j] = sum over the normal  block of Xq[m,p]*Wq[j,p]
+ *     r = (float)acc_o * s_outlier[j];  r = fmaf((float)acc_n, s_normal[j], r);
+ *     Y[m,j] = fmaf(r, s_x[m], bias[j])   stored as fp32, or rounded to bf16 (nearest-even)
+ *   Xq, Wq  in  packed i8 for the same (K, K_o); 16-byte aligned, strides multiples of 16
+ *   s_x     in  f32 [M];  s_normal, s_outlier in f32 [N];  bias in f32 [N] or NULL (+0.0f)
+ *   Y       out [M, ldy] of `ydt`; 16-byte aligned, ldy*sizeof(elem) % 16 == 0
+ *   dbg_acc_normal, dbg_acc_outlier   out i32 [M,N] (dense, ld = N) or NULL: raw accumulators
+ *                                     for parity checks; pass NULL when timing.
+ * Fully asynchronous on `stream`.
+ */
+qarvd_status qarvd_w8a8_dual_gemm(const int8_t *Xq, int64_t ldxq, const float *s_x,
+                                  const int8_t *Wq, int64_t ldwq, const float *s_normal,
+                                  const float *s_outlier, const float *bias, int32_t M, int32_t N,
+                                  int32_t K, int32_t K_o, void *Y, qarvd_dtype ydt, int64_t ldy,
+                                  int32_t *dbg_acc_normal, int32_t *dbg_acc_outlier, void *stream);
+
+/*
+ * Same operation with the kernel variant chosen by the caller instead of the built-in
+ * heuristic (variant 0 = heuristic).  qarvd_gemm_num_variants() is the count of selectable
+ * variants (1..count); qarvd_gemm_variant_name(i) describes one.  A variant that cannot run
+ * the given shape returns QARVD_ERR_UNSUPPORTED.  Used by the parity tests and the tuner.
+ */
+qarvd_status qarvd_w8a8_dual_gemm_variant(int32_t variant, const int8_t *Xq, int64_t ldxq,
+                                          const float *s_x, const int8_t *Wq, int64_t ldwq,
+                                          const float *s_normal, const float *s_outlier,
+                                          const float *bias, int32_t M, int32_t N, int32_t K,
+                                          int32_t K_o, void *Y, qarvd_dtype ydt, int64_t ldy,
+                                          int32_t *dbg_acc_normal, int32_t *dbg_acc_outlier,
+                                          void *stream);
+int32_t qarvd_gemm_num_variants(void);
+const char *qarvd_gemm_variant_name(int32_t variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QARVD_H */

@@ -1,0 +1,21 @@
+"""MI355X-native dual-scale W8A8 linear layer of Q-ARVD: thin Python binding over libqarvd.so.
+
+The three operations live in hand-written HIP kernels behind a C ABI (``include/qarvd.h``); this
+package only marshals arguments.  PyTorch supplies device memory and streams, nothing else.
+"""
+from .binding import (  # noqa: F401
+    DualScaleWeight,
+    QarvdError,
+    gemm_num_variants,
+    gemm_variant_name,
+    lib_path,
+    load_library,
+    packed_k,
+    packed_normal_offset,
+    quant_act,
+    quant_act_static,
+    quantize_weight,
+    quantize_weight_workspace,
+    w8a8_dual_gemm,
+    w8a8_linear,
+)

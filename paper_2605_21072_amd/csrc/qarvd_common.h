@@ -1,0 +1,68 @@
+// Shared host/device helpers of the gfx950 library (not used by the CPU oracle).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/qarvd.h"
+
+#define QARVD_HIP_TRY(expr)                      \
+    do {                                         \
+        hipError_t e__ = (expr);                 \
+        if (e__ != hipSuccess) {                 \
+            (void)hipGetLastError();             \
+            return QARVD_ERR_HIP;                \
+        }                                        \
+    } while (0)
+
+static inline qarvd_status qarvd_launch_status()
+{
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? QARVD_OK : QARVD_ERR_HIP;
+}
+
+static inline bool qarvd_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static inline int32_t qarvd_round_up(int32_t x, int32_t m) { return (x + m - 1) / m * m; }
+
+// Packed-row geometry (see the layout comment in qarvd.h).
+struct PackedK {
+    int32_t K, K_o;
+    int32_t n_off;   // start of the normal block
+    int32_t kp;      // packed extent, multiple of 128
+};
+static inline PackedK qarvd_packed(int32_t K, int32_t K_o)
+{
+    PackedK g;
+    g.K = K;
+    g.K_o = K_o;
+    g.n_off = qarvd_round_up(K_o, 32);
+    g.kp = qarvd_round_up(g.n_off + (K - K_o), 128);
+    return g;
+}
+
+// Eq. (quantization), symmetric, z = 0, clip to [-127,127], round-half-even; s == 0 -> 0.
+// The division is the IEEE-correct fp32 division hipcc emits by default.
+__device__ __forceinline__ int quantize_i8(float x, float s)
+{
+    if (s == 0.0f) return 0;
+    float r = rintf(x / s);
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// fp32 -> bf16 bits, round-to-nearest-even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
