@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the dual-scale W8A8 linear on one MI355X.
+
+A "step" is one pass of the online hot path (activation quantization with the gather-permute,
+then the dual INT8 GEMM with its dequant epilogue) over every layer of the workload: the six
+linears of a Wan-1.3B-style DiT block for one 3-latent-frame chunk (M = 4680 tokens), each at
+the four planted outlier counts {0, 4, 16, 64} -- 24 layers, 48 kernel launches.  The offline
+weight step (detection, permutation, dual scales) runs once before the timed region.  All
+inputs are resident in HBM when timing starts.
+
+Prints ONE JSON line.  `value` = sum over layers of 2*M*N*K divided by the step time (INT8 TOPS
+of the whole linear, quantization included).  Also reported: the GEMM alone on the target shape
+(M=4680, 1536 -> 8960) against the dense INT8 MFMA peak, the bf16 torch.nn.functional.linear
+comparator, the activation-quant kernel against the HBM peak, and the CPU oracle on the host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, published
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload config (2 = the one the metric is quoted on)")
+    ap.add_argument("--layers", type=str, default="", help="comma-separated layer names to restrict the step to")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bf16", action="store_true")
+    ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant (0 = heuristic)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (token rows would shard across GPUs with no exchange step); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2605_21072_amd as q
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    q.load_library()
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    specs = wl.config_layers(args.config)
+    if args.layers:
+        keep = set(args.layers.split(","))
+        specs = [s for s in specs if s.name in keep]
+    assert specs, "no layers selected"
+
+    # ---- offline: synthetic tensors -> HBM, weight step once per layer ---------------------
+    layers = []
+    for s in specs:
+        L = wl.make_layer(s)
+        W = torch.from_numpy(L["W"]).to(dev)
+        w = q.quantize_weight(W, want_norms=False)
+        X = torch.from_numpy(L["X"]).to(dev)
+        layer = dict(spec=s, w=w, X=X, bias=torch.from_numpy(L["bias"]).to(dev),
+                     perm=w.perm if w.K_o > 0 else None,
+                     Xq=torch.empty((s.M, q.packed_k(s.K, w.K_o)), dtype=torch.int8, device=dev),
+                     sx=torch.empty(s.M, dtype=torch.float32, device=dev),
+                     Y=torch.empty((s.M, s.N), dtype=torch.bfloat16, device=dev))
+        if not args.no_bf16:
+            layer["Wb"] = W.to(torch.bfloat16)
+            layer["Xb"] = X.to(torch.bfloat16)
+            layer["bb"] = layer["bias"].to(torch.bfloat16)
+        del W
+        layers.append(layer)
+    torch.cuda.synchronize()
+
+    def run_quant(l):
+        q.quant_act(l["X"], l["perm"], l["w"].K_o, Xq=l["Xq"], s_x=l["sx"])
+
+    def run_gemm(l):
+        q.w8a8_dual_gemm(l["Xq"], l["sx"], l["w"], l["bias"], l["spec"].M, Y=l["Y"], variant=args.variant)
+
+    def step():
+        for l in layers:
+            run_quant(l)
+            run_gemm(l)
+
+    # ---- timed region: W warm-up steps, then exactly K steps between synchronisations ------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = 1e3 * wall / args.steps
+    total_ops = sum(2.0 * l["spec"].macs for l in layers)
+    value = total_ops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- same steps again with an event after every launch: per-kernel durations -----------
+    nl = len(layers)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2 * nl + 1)] for _ in range(args.steps)]
+    for s_i in range(args.steps):
+        ev[s_i][0].record()
+        for i, l in enumerate(layers):
+            run_quant(l)
+            ev[s_i][2 * i + 1].record()
+            run_gemm(l)
+            ev[s_i][2 * i + 2].record()
+    torch.cuda.synchronize()
+    quant_us = np.zeros(nl)
+    gemm_us = np.zeros(nl)
+    for s_i in range(args.steps):
+        for i in range(nl):
+            quant_us[i] += 1e3 * ev[s_i][2 * i].elapsed_time(ev[s_i][2 * i + 1])
+            gemm_us[i] += 1e3 * ev[s_i][2 * i + 1].elapsed_time(ev[s_i][2 * i + 2])
+    quant_us /= args.steps
+    gemm_us /= args.steps
+
+    # ---- bf16 comparator: the vendor GEMM a user would otherwise call ----------------------
+    bf16_us = [None] * nl
+    if not args.no_bf16:
+        F = torch.nn.functional
+        for i, l in enumerate(layers):
+            for _ in range(3):
+                F.linear(l["Xb"], l["Wb"], l["bb"])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                F.linear(l["Xb"], l["Wb"], l["bb"])
+            e1.record()
+            torch.cuda.synchronize()
+            bf16_us[i] = 1e3 * e0.elapsed_time(e1) / args.steps
+
+    per_layer = []
+    for i, l in enumerate(layers):
+        s = l["spec"]
+        ops = 2.0 * s.macs
+        act_bytes = 5.0 * s.M * s.K + 4.0 * s.M
+        d = dict(name=s.name, M=s.M, K=s.K, N=s.N, K_o=l["w"].K_o,
+                 gemm_us=round(float(gemm_us[i]), 2), quant_us=round(float(quant_us[i]), 2),
+                 gemm_tops=round(ops / gemm_us[i] / 1e6, 1),
+                 gemm_frac_peak=round(ops / gemm_us[i] / 1e6 / PEAK_INT8_TOPS, 4),
+                 quant_gbs=round(act_bytes / quant_us[i] / 1e3, 1))
+        if bf16_us[i] is not None:
+            d["bf16_us"] = round(bf16_us[i], 2)
+            d["speedup_gemm_vs_bf16"] = round(bf16_us[i] / gemm_us[i], 3)
+            d["speedup_linear_vs_bf16"] = round(bf16_us[i] / (gemm_us[i] + quant_us[i]), 3)
+        per_layer.append(d)
+
+    # dominant kernel: the GEMM at the target shape (M=4680, 1536 -> 8960)
+    tgt = [i for i, l in enumerate(layers) if (l["spec"].K, l["spec"].N) == (wl.HIDDEN, wl.FFN)]
+    dom = tgt if tgt else [int(np.argmax(gemm_us))]
+    dom_us = float(np.mean(gemm_us[dom]))
+    s0 = layers[dom[0]]["spec"]
+    dom_ops = 2.0 * s0.macs
+    achieved = dom_ops / dom_us / 1e6
+    roofline = dict(bound="mfma", kernel="qarvd_w8a8_dual_gemm M=%d K=%d N=%d" % (s0.M, s0.K, s0.N),
+                    achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TOP/s",
+                    frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=None, avg_launch_us=round(dom_us, 2))
+    # the memory-bound kernel of the path
+    qi = int(np.argmax(quant_us))
+    sq = layers[qi]["spec"]
+    quant_roof = dict(bound="hbm", kernel="qarvd_quant_act M=%d K=%d" % (sq.M, sq.K),
+                      achieved=per_layer[qi]["quant_gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
+                      frac=round(per_layer[qi]["quant_gbs"] / PEAK_HBM_GBS, 4), avg_launch_us=per_layer[qi]["quant_us"])
+
+    out = dict(metric="INT8 TOPS of the dual-scale W8A8 linear (quant_act + dual GEMM); % of dense INT8 MFMA peak; "
+                      "speedup vs bf16",
+               value=round(value, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(ms_per_step, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="int8", data="synthetic",
+               config=dict(workload="config %d: %d DiT-block linears (M=%d tokens), quant_act + dual GEMM each"
+                           % (args.config, nl, specs[0].M),
+                           layers=nl, launches_per_step=2 * nl, out_dtype="bf16", gemm_variant=args.variant),
+               frac_int8_peak=round(value / PEAK_INT8_TOPS, 4),
+               roofline=roofline, quant_act_roofline=quant_roof)
+    if tgt:
+        t = [per_layer[i] for i in tgt]
+        out["target_layer"] = dict(shape="M=4680 K=1536 N=8960",
+                                   gemm_tops=round(float(np.mean([x["gemm_tops"] for x in t])), 1),
+                                   gemm_frac_peak=round(float(np.mean([x["gemm_frac_peak"] for x in t])), 4),
+                                   speedup_gemm_vs_bf16=None if args.no_bf16 else
+                                   round(float(np.mean([x["speedup_gemm_vs_bf16"] for x in t])), 3),
+                                   speedup_linear_vs_bf16=None if args.no_bf16 else
+                                   round(float(np.mean([x["speedup_linear_vs_bf16"] for x in t])), 3))
+    out["paper_context"] = "paper reports 1.30x end-to-end INT8 speedup and 1.97x size reduction on an NVIDIA A6000 " \
+                           "with Triton kernels (whole pipeline, not this kernel)"
+
+    # ---- CPU oracle on the host cores (reported baseline, bounded sample) -------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        smp = [l for l in layers if l["spec"].n_outlier == 16] or layers[:1]
+        cpu_ops, cpu_t = 0.0, 0.0
+        for l in smp:
+            s = l["spec"]
+            Lh = wl.make_layer(s)
+            qw = oracle.quantize_weight(Lh["W"])            # offline, untimed (as on the GPU side)
+            t1 = time.perf_counter()
+            Xq, sx = oracle.quant_act(Lh["X"], qw["perm"])
+            oracle.dual_gemm(Xq, sx, qw["Wq"], qw["s_normal"], qw["s_outlier"], Lh["bias"], qw["K_o"],
+                             want_acc=False, want_f32=False, want_bf16=True)
+            cpu_t += time.perf_counter() - t1
+            cpu_ops += 2.0 * s.macs
+        out["cpu_baseline"] = dict(value=round(cpu_ops / cpu_t / 1e12, 5), unit="TOPS", cores=oracle.num_threads(),
+                                   kind="oracle", seconds=round(cpu_t, 2),
+                                   sample="the %d layers with 16 planted outliers (one DiT block: q,k,v,o,ffn_up,"
+                                          "ffn_down at M=%d), quant_act + dual_gemm, full size" % (len(smp), smp[0]["spec"].M))
+    out["layers"] = per_layer
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -10,7 +10,7 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libqarvd.so"
-SOURCES = ["quant_act.hip", "quantize_weight.hip", "gemm.hip"]
+SOURCES = ["quant_act.hip", "quantize_weight.hip", "gemm_api.hip", "gemm_staged.hip", "gemm_dma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

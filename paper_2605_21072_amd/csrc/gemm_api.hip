@@ -1,0 +1,114 @@
+// C entry points of the dual-scale W8A8 GEMM: argument validation, variant table and heuristic.
+#include "gemm_common.h"
+
+using namespace qarvd_gemm;
+
+namespace {
+
+const Variant kVariants[] = {
+    // name, BM, BN, widest outlier block (packed bytes), needs vector output, launcher
+    {"staged 256x128 dual", 256, 128, 1 << 30, false, launch_staged<256, 128, 2, 2, true>},
+    {"staged 128x128 dual", 128, 128, 1 << 30, false, launch_staged<128, 128, 2, 2, true>},
+    {"staged 256x128 single", 256, 128, 0, false, launch_staged<256, 128, 2, 2, false>},
+    {"staged 128x128 single", 128, 128, 0, false, launch_staged<128, 128, 2, 2, false>},
+    {"lds-direct 256x128 dual", 256, 128, 128, true, launch_dma<256, 128, true>},
+    {"lds-direct 256x128 single", 256, 128, 0, true, launch_dma<256, 128, false>},
+    {"lds-direct 192x128 dual", 192, 128, 128, true, launch_dma<192, 128, true>},
+    {"lds-direct 192x128 single", 192, 128, 0, true, launch_dma<192, 128, false>},
+    {"lds-direct 128x128 dual", 128, 128, 128, true, launch_dma<128, 128, true>},
+    {"lds-direct 128x128 single", 128, 128, 0, true, launch_dma<128, 128, false>},
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+bool vector_out_ok(const GemmArgs &g, qarvd_dtype ydt)
+{
+    const size_t esz = ydt == QARVD_F32 ? 4 : 2;
+    return (g.N % 8) == 0 && qarvd_aligned16(g.Y) && ((g.ldy * esz) % 16) == 0 && qarvd_aligned16(g.s_n) &&
+           qarvd_aligned16(g.s_o) && qarvd_aligned16(g.bias);
+}
+
+bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)
+{
+    if (g.n_off > v.max_n_off) return false;
+    if (v.needs_vector_out && !vector_out_ok(g, ydt)) return false;
+    return true;
+}
+
+// Heuristic: LDS-direct kernels when the shape allows them; the tile height that wastes the fewest
+// MFMA cycles on the last partial wave of tiles over the chip's 256 CUs (two workgroups each).
+int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
+{
+    const bool dual = g.n_off > 0;
+    if (g.n_off <= 128 && vector_out_ok(g, ydt)) {
+        const int cand[3] = {dual ? 5 : 6, dual ? 7 : 8, dual ? 9 : 10};
+        const int bm[3] = {256, 192, 128};
+        int best = cand[0];
+        double best_cost = 1e300;
+        for (int c = 0; c < 3; ++c) {
+            const long tiles = (long)((g.M + bm[c] - 1) / bm[c]) * ((g.N + 127) / 128);
+            const long rounds = (tiles + 255) / 256;             // tiles per CU, busiest CU
+            double cost = (double)rounds * bm[c];                 // MFMA time of the busiest CU
+            cost *= 1.0 + 16.0 / bm[c];                           // smaller tiles re-read operands more often
+            if (cost < best_cost) {
+                best_cost = cost;
+                best = cand[c];
+            }
+        }
+        return best;
+    }
+    const long tiles_big = (long)((g.M + 255) / 256) * ((g.N + 127) / 128);
+    if (dual) return tiles_big >= 256 ? 1 : 2;
+    return tiles_big >= 256 ? 3 : 4;
+}
+
+}  // namespace
+
+extern "C" int32_t qarvd_gemm_num_variants(void) { return kNumVariants; }
+
+extern "C" const char *qarvd_gemm_variant_name(int32_t variant)
+{
+    if (variant < 1 || variant > kNumVariants) return "";
+    return kVariants[variant - 1].name;
+}
+
+extern "C" qarvd_status qarvd_w8a8_dual_gemm_variant(int32_t variant, const int8_t *Xq, int64_t ldxq,
+                                                     const float *s_x, const int8_t *Wq, int64_t ldwq,
+                                                     const float *s_normal, const float *s_outlier,
+                                                     const float *bias, int32_t M, int32_t N, int32_t K,
+                                                     int32_t K_o, void *Y, qarvd_dtype ydt, int64_t ldy,
+                                                     int32_t *dbg_acc_normal, int32_t *dbg_acc_outlier,
+                                                     void *stream)
+{
+    if (!Xq || !Wq || !s_x || !s_normal || !s_outlier || !Y) return QARVD_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0 || K <= 0 || K > QARVD_MAX_K || K_o < 0 || K_o > K) return QARVD_ERR_INVALID_ARG;
+    if (variant < 0 || variant > kNumVariants) return QARVD_ERR_INVALID_ARG;
+    const PackedK pk = qarvd_packed(K, K_o);
+    if (ldxq < pk.kp || ldwq < pk.kp || ldy < N) return QARVD_ERR_INVALID_ARG;
+    if (ydt != QARVD_F32 && ydt != QARVD_BF16) return QARVD_ERR_UNSUPPORTED;
+    if (!qarvd_aligned16(Xq) || !qarvd_aligned16(Wq) || (ldxq % 16) || (ldwq % 16)) return QARVD_ERR_UNSUPPORTED;
+    const size_t esz = ydt == QARVD_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(Y) % esz) return QARVD_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(s_x) | reinterpret_cast<uintptr_t>(s_normal) | reinterpret_cast<uintptr_t>(s_outlier) |
+         reinterpret_cast<uintptr_t>(bias) | reinterpret_cast<uintptr_t>(dbg_acc_normal) |
+         reinterpret_cast<uintptr_t>(dbg_acc_outlier)) & 3u)
+        return QARVD_ERR_UNSUPPORTED;
+    GemmArgs g;
+    g.Xq = Xq; g.Wq = Wq; g.s_x = s_x; g.s_n = s_normal; g.s_o = s_outlier; g.bias = bias;
+    g.Y = Y; g.dbg_n = dbg_acc_normal; g.dbg_o = dbg_acc_outlier;
+    g.ldxq = ldxq; g.ldwq = ldwq; g.ldy = ldy; g.M = M; g.N = N; g.n_off = pk.n_off; g.kp = pk.kp;
+    g.tiles_m = g.tiles_n = 0;
+    if (variant == 0) variant = pick_variant(g, ydt);
+    const Variant &v = kVariants[variant - 1];
+    if (!variant_fits(v, g, ydt)) return QARVD_ERR_UNSUPPORTED;
+    return v.launch(g, ydt, reinterpret_cast<hipStream_t>(stream));
+}
+
+extern "C" qarvd_status qarvd_w8a8_dual_gemm(const int8_t *Xq, int64_t ldxq, const float *s_x,
+                                             const int8_t *Wq, int64_t ldwq, const float *s_normal,
+                                             const float *s_outlier, const float *bias, int32_t M, int32_t N,
+                                             int32_t K, int32_t K_o, void *Y, qarvd_dtype ydt, int64_t ldy,
+                                             int32_t *dbg_acc_normal, int32_t *dbg_acc_outlier, void *stream)
+{
+    return qarvd_w8a8_dual_gemm_variant(0, Xq, ldxq, s_x, Wq, ldwq, s_normal, s_outlier, bias, M, N, K, K_o, Y, ydt,
+                                        ldy, dbg_acc_normal, dbg_acc_outlier, stream);
+}
