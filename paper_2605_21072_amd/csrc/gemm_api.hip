@@ -11,12 +11,16 @@ const Variant kVariants[] = {
     {"staged 128x128 dual", 128, 128, 1 << 30, false, launch_staged<128, 128, 2, 2, true>},
     {"staged 256x128 single", 256, 128, 0, false, launch_staged<256, 128, 2, 2, false>},
     {"staged 128x128 single", 128, 128, 0, false, launch_staged<128, 128, 2, 2, false>},
-    {"lds-direct 256x128 dual", 256, 128, 128, true, launch_dma<256, 128, true>},
-    {"lds-direct 256x128 single", 256, 128, 0, true, launch_dma<256, 128, false>},
-    {"lds-direct 192x128 dual", 192, 128, 128, true, launch_dma<192, 128, true>},
-    {"lds-direct 192x128 single", 192, 128, 0, true, launch_dma<192, 128, false>},
-    {"lds-direct 128x128 dual", 128, 128, 128, true, launch_dma<128, 128, true>},
-    {"lds-direct 128x128 single", 128, 128, 0, true, launch_dma<128, 128, false>},
+    {"lds-direct 256x128 (4 waves, 3 stages) dual", 256, 128, 128, true, launch_dma<256, 128, 2, 2, 3, true>},
+    {"lds-direct 256x128 (4 waves, 3 stages) single", 256, 128, 0, true, launch_dma<256, 128, 2, 2, 3, false>},
+    {"lds-direct 192x128 (4 waves, 3 stages) dual", 192, 128, 128, true, launch_dma<192, 128, 2, 2, 3, true>},
+    {"lds-direct 192x128 (4 waves, 3 stages) single", 192, 128, 0, true, launch_dma<192, 128, 2, 2, 3, false>},
+    {"lds-direct 128x128 (4 waves, 4 stages) dual", 128, 128, 128, true, launch_dma<128, 128, 2, 2, 4, true>},
+    {"lds-direct 128x128 (4 waves, 4 stages) single", 128, 128, 0, true, launch_dma<128, 128, 2, 2, 4, false>},
+    {"lds-direct 256x256 (8 waves, 4 stages) dual", 256, 256, 128, true, launch_dma<256, 256, 2, 4, 4, true>},
+    {"lds-direct 256x256 (8 waves, 4 stages) single", 256, 256, 0, true, launch_dma<256, 256, 2, 4, 4, false>},
+    {"lds-direct 256x256 (4 waves of 128x128, 4 stages) dual", 256, 256, 128, true, launch_dma<256, 256, 2, 2, 4, true>},
+    {"lds-direct 256x256 (4 waves of 128x128, 4 stages) single", 256, 256, 0, true, launch_dma<256, 256, 2, 2, 4, false>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 

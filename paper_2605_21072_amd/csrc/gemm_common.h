@@ -79,7 +79,7 @@ struct Variant {
 // launchers defined in gemm_staged.hip / gemm_dma.hip
 template <int BM, int BN, int WM, int WN, bool DUAL>
 qarvd_status launch_staged(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
-template <int BM, int BN, bool DUAL>
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
 qarvd_status launch_dma(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 
 }  // namespace qarvd_gemm

@@ -1,42 +1,51 @@
-// LDS-direct variant of the dual-scale W8A8 GEMM for gfx950 (appendix "Quantization Kernels",
-// kernel (ii); Eq. (dual_scale)).
+// LDS-direct dual-scale W8A8 GEMM for gfx950 (appendix "Quantization Kernels", kernel (ii);
+// Eq. (dual_scale)): INT8 x INT8 -> INT32 on v_mfma_i32_32x32x32_i8 with an fp32 dequant epilogue.
 //
-// Design (two 256-thread workgroups per CU so that one workgroup's epilogue -- conversion,
-// packing and the output store -- runs under the other's MFMA loop):
-//   * Operand tiles of 64 K-bytes go from global memory straight into LDS with
-//     global_load_lds_dwordx4 (no VGPR staging), three stages deep.  One such instruction fills
-//     1 KB of LDS contiguously (16 rows x 64 B); the XOR swizzle that keeps the later 32-row
-//     fragment reads off the same banks is applied on the GLOBAL side: the lane that fills slot s
-//     of row r fetches 16-byte chunk s ^ swz64(r) of that row.
-//   * Waits are explicit: s_waitcnt vmcnt(n) for the tile about to be consumed, then a bare
-//     s_barrier (no fence, which would drain every outstanding load), then the loads of the
-//     tile two steps ahead are issued into the stage everybody has just finished reading.
-//   * The wave tile is (BM/2) x (BN/2) with the W fragment as the MFMA A operand and the X fragment
-//     as the B operand, so a lane owns ONE token row and four consecutive output features per
-//     register quad: the per-token scale is a per-lane scalar, the per-feature scales and bias are
-//     float4 loads, and four results pack into one 8-byte LDS write.
-//   * Only the normal-range sum lives in registers during the K loop.  The tiles that contain
-//     the outlier range (at most two, since the outlier block is <= 128 bytes here) are visited
-//     LAST, so they are still resident in LDS when the loop ends; the epilogue computes each
-//     32x32 block's outlier sum into a 16-register temporary with 1-4 MFMAs and merges the two
-//     INT32 accumulators through
+// One kernel template, instantiated for several workgroup shapes:
+//   BM x BN  workgroup tile;  WM x WN wavefronts, each owning (BM/WM) x (BN/WN) = TM x TN MFMA
+//            blocks of 32 x 32 (the accumulators are the only large register set);
+//   NSTAGE   LDS stages of 64 K-bytes per operand row, filled NSTAGE-1 stages ahead.
+// The big DiT shapes use 256 x 256 with eight waves (one workgroup per CU, 128 KB of stages):
+// a 256 x 256 tile needs half the L1/L2 operand traffic per MAC of 256 x 128, and the MI355X
+// retires 4096 INT8 MACs per clock per CU against 64 B/clk of vector L1.  Smaller shapes use
+// four-wave tiles, two workgroups per CU.
+//
+// Data path
+//   * global -> LDS with global_load_lds_dwordx4, no VGPR staging.  One instruction fills 1 KB of
+//     LDS contiguously (16 rows x 64 B); the XOR swizzle that keeps the 32-row fragment reads off
+//     the same banks is applied on the GLOBAL side: the lane that fills slot s of row r fetches
+//     16-byte chunk s ^ swz64(r) of that row.  Measured load-to-use latency of these loads is
+//     0.7 us from L2 and 1-1.4 us from memory, so NSTAGE-1 stages are kept in flight.
+//   * explicit waits: s_waitcnt vmcnt(n) for the stage about to be read, then a bare s_barrier
+//     (a fence would drain every outstanding load), then the refill of the stage everybody
+//     finished reading one iteration ago.  The steady-state loop is a single basic block.
+//   * W fragment = MFMA A operand, X fragment = B operand, so a lane owns ONE token row and four
+//     consecutive output features per register quad: the per-token scale is a per-lane scalar, the
+//     per-feature scales and bias are float4 LDS reads, four results pack into one 8-byte write.
+//   * only the normal-range sum lives in registers through the K loop.  The (at most two)
+//     64-byte tiles holding the outlier range are visited LAST and stay resident in LDS; the
+//     epilogue sums each 32 x 32 block's outlier k-steps into a 16-register temporary (1-4
+//     MFMAs) and merges the two INT32 accumulators as
 //         r = (float)acc_o * s_o;  r = fmaf((float)acc_n, s_n, r);  y = fmaf(r, s_x, bias).
-//   * Results are transposed through a wave-private LDS patch (row stride 144 B: conflict-free
-//     8-byte writes and 16-byte reads) and leave as 16-byte stores covering whole 128-byte row
-//     segments.
+//   * scales and bias are parked in LDS at kernel start; bf16 results are packed with
+//     v_cvt_pk_bf16_f32 (round-to-nearest-even), transposed through a wave-private LDS patch
+//     (row stride 144 B: conflict-free 8-byte writes and 16-byte reads) and stored as 16-byte
+//     pieces covering whole 128-byte row segments.
 #include "gemm_common.h"
 
 namespace qarvd_gemm {
 
 namespace {
 
-constexpr int BKD = 64;      // K bytes per stage
-constexpr int NSTAGE = 3;
+constexpr int BKD = 64;                   // K bytes per stage row
 constexpr int PATCH_RS = 144;             // bytes per row of the output patch (128 + 16 pad)
 constexpr int PATCH_BYTES = 32 * PATCH_RS;
 
 #define QARVD_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define QARVD_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 
 // Swizzle for 64-byte LDS rows (four 16-byte slots): any 8 consecutive rows spread over all
 // (row parity, slot) pairs and any 16 consecutive rows over all (row mod 4, slot) pairs.
@@ -45,51 +54,77 @@ __device__ __forceinline__ int swz64(int r) { return (((r >> 1) ^ (r >> 3)) & 1)
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14]).
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
-__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(63 | (7 << 4) | (0 << 8) | (3 << 14)); }
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14)); }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+// two fp32 -> packed bf16, round-to-nearest-even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b)
 {
-    return f32_to_bf16_bits(a) | (f32_to_bf16_bits(b) << 16);
+    v2f f = {a, b};
+    v2bf h = __builtin_convertvector(f, v2bf);
+    return __builtin_bit_cast(uint32_t, h);
 }
 
-template <int BM, int BN, bool DUAL, typename OutT>
-__global__ __launch_bounds__(TPB, 2) void gemm_dma_kernel(GemmArgs g)
+template <int BM, int BN, int WM, int WN, int NSTAGE>
+struct Geo {
+    static constexpr int NW = WM * WN;                 // wavefronts
+    static constexpr int THREADS = 64 * NW;
+    static constexpr int WTM = BM / WM, WTN = BN / WN; // wave tile
+    static constexpr int TM = WTM / 32, TN = WTN / 32; // 32x32 blocks per wave
+    static constexpr int NA = BM / 16 / NW, NB = BN / 16 / NW;   // LDS-direct loads per wave per stage
+    static constexpr int NLOAD = NA + NB;
+    static constexpr int STG = (BM + BN) * BKD;
+    static constexpr int PATCHES = NW * PATCH_BYTES;
+    // where the output patches go: inside one free stage, split over two free stages, or behind the stages
+    static constexpr bool PATCH_ONE = PATCHES <= STG;
+    static constexpr bool PATCH_TWO = !PATCH_ONE && NSTAGE >= 4 && PATCHES <= 2 * STG && (NW % 2) == 0;
+    static constexpr int PATCH_EXTRA = (PATCH_ONE || PATCH_TWO) ? 0 : PATCHES;
+    static constexpr int SCALES_OFF = NSTAGE * STG + PATCH_EXTRA;
+    static constexpr int NSCALE = BM + 3 * BN;
+    static constexpr int LDS_BYTES = SCALES_OFF + NSCALE * (int)sizeof(float);
+    static constexpr int SPT = (NSCALE + THREADS - 1) / THREADS;   // scale values per thread
+    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "row groups must divide over the waves");
+    static_assert(WTM % 32 == 0 && WTN % 64 == 0, "wave tile is TM x TN blocks, TN even (a patch pass holds 64 bf16 columns)");
+    // accumulators beyond 128 registers per lane need the whole register file: one wave per SIMD
+    static constexpr int WAVES_PER_EU = (TM * TN * 16 > 128) ? 1 : 2;
+    static_assert(NSTAGE >= 3, "two head tiles plus one free stage");
+};
+
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool DBG, typename OutT>
+__global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_PER_EU)) void gemm_dma_kernel(GemmArgs g)
 {
-    constexpr int WTM = BM / 2, WTN = BN / 2;      // 2 x 2 wavefronts
-    constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 blocks per wave
-    constexpr int NA = BM / 64, NB = BN / 64;      // LDS-direct loads per wave per stage
-    constexpr int NLOAD = NA + NB;
-    constexpr int STG = (BM + BN) * BKD;
-    constexpr bool PATCH_IN_STAGE = 4 * PATCH_BYTES <= STG;   // else the patches follow the stages
-    constexpr int SCALES_OFF = NSTAGE * STG + (PATCH_IN_STAGE ? 0 : 4 * PATCH_BYTES);
+    using G = Geo<BM, BN, WM, WN, NSTAGE>;
+    constexpr int TM = G::TM, TN = G::TN, NA = G::NA, NB = G::NB, NW = G::NW, STG = G::STG;
+    constexpr int AHEAD = NSTAGE - 1;                  // stages in flight
     extern __shared__ __align__(16) unsigned char smem[];
-    float *sx_lds = reinterpret_cast<float *>(smem + SCALES_OFF);   // [BM]
-    float *sn_lds = sx_lds + BM;                                      // [BN]
-    float *so_lds = sn_lds + BN;                                      // [BN]
-    float *bs_lds = so_lds + BN;                                      // [BN]
+    float *sc_lds = reinterpret_cast<float *>(smem + G::SCALES_OFF);   // s_x[BM] | s_n[BN] | s_o[BN] | bias[BN]
+    const float *sx_lds = sc_lds, *sn_lds = sc_lds + BM, *so_lds = sc_lds + BM + BN, *bs_lds = sc_lds + BM + 2 * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     int tm, tn;
     tile_coords(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
-    // ---- scales and bias of this tile: global -> registers now, -> LDS after the first tile
-    // loads have been issued (so their latency overlaps), read back by the epilogue ----------
-    float r_sx = 0.f, r_sn = 0.f, r_so = 0.f, r_bs = 0.f;
-    if (tid < BM) r_sx = g.s_x[min(m0 + tid, g.M - 1)];
-    if (tid < BN) {
-        const int nc = min(n0 + tid, g.N - 1);
-        r_sn = g.s_n[nc];
-        r_so = g.s_o[nc];
-        if (g.bias) r_bs = g.bias[nc];
+    // ---- scales and bias of this tile: global -> registers now, -> LDS once the first stage
+    // loads are in flight (so the latencies overlap); read back by the epilogue --------------
+    float r_s[G::SPT];
+#pragma unroll
+    for (int u = 0; u < G::SPT; ++u) {
+        const int e = tid + u * G::THREADS;
+        float v = 0.f;
+        if (e < BM) v = g.s_x[min(m0 + e, g.M - 1)];
+        else if (e < BM + BN) v = g.s_n[min(n0 + e - BM, g.N - 1)];
+        else if (e < BM + 2 * BN) v = g.s_o[min(n0 + e - BM - BN, g.N - 1)];
+        else if (e < BM + 3 * BN && g.bias) v = g.bias[min(n0 + e - BM - 2 * BN, g.N - 1)];
+        r_s[u] = v;
     }
 
     // ---- LDS-direct load addressing -------------------------------------------------------
-    // Load i of this wave fills rows (4*i + wave)*16 .. +16 of the operand tile; lane l fills slot
+    // Load i of this wave fills rows (NW*i + wave)*16 .. +16 of the operand tile; lane l fills slot
     // (l & 3) of row (l >> 2) with global chunk (l & 3) ^ swz64(l >> 2).
     const int drow = lane >> 2;
     const int dchunk = ((lane & 3) ^ swz64(drow)) << 4;
@@ -97,26 +132,26 @@ __global__ __launch_bounds__(TPB, 2) void gemm_dma_kernel(GemmArgs g)
     const int8_t *pb[NB];
 #pragma unroll
     for (int i = 0; i < NA; ++i)
-        pa[i] = g.Xq + (size_t)min(m0 + (4 * i + wave) * 16 + drow, g.M - 1) * g.ldxq + dchunk;
+        pa[i] = g.Xq + (size_t)min(m0 + (NW * i + wave) * 16 + drow, g.M - 1) * g.ldxq + dchunk;
 #pragma unroll
     for (int i = 0; i < NB; ++i)
-        pb[i] = g.Wq + (size_t)min(n0 + (4 * i + wave) * 16 + drow, g.N - 1) * g.ldwq + dchunk;
+        pb[i] = g.Wq + (size_t)min(n0 + (NW * i + wave) * 16 + drow, g.N - 1) * g.ldwq + dchunk;
 
     auto issue = [&](int tile, int stage) {
         unsigned char *sb = smem + stage * STG;
         const size_t koff = (size_t)tile * BKD;
 #pragma unroll
         for (int i = 0; i < NA; ++i)
-            __builtin_amdgcn_global_load_lds(QARVD_GPTR(pa[i] + koff), QARVD_LPTR(sb + (4 * i + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(QARVD_GPTR(pa[i] + koff), QARVD_LPTR(sb + (NW * i + wave) * 1024), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            __builtin_amdgcn_global_load_lds(QARVD_GPTR(pb[i] + koff), QARVD_LPTR(sb + BM * BKD + (4 * i + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(QARVD_GPTR(pb[i] + koff), QARVD_LPTR(sb + BM * BKD + (NW * i + wave) * 1024), 16, 0, 0);
     };
 
     // ---- fragment addressing --------------------------------------------------------------
     const int frow = lane & 31, fhalf = lane >> 5, fsw = swz64(frow);
-    const int x_base = (wm * WTM + frow) * BKD;               // X rows: MFMA B operand
-    const int w_base = BM * BKD + (wn * WTN + frow) * BKD;    // W rows: MFMA A operand
+    const int x_base = (wm * G::WTM + frow) * BKD;               // X rows: MFMA B operand
+    const int w_base = BM * BKD + (wn * G::WTN + frow) * BKD;    // W rows: MFMA A operand
     int coff[2];
     coff[0] = ((0 | fhalf) ^ fsw) << 4;
     coff[1] = ((2 | fhalf) ^ fsw) << 4;
@@ -146,74 +181,94 @@ __global__ __launch_bounds__(TPB, 2) void gemm_dma_kernel(GemmArgs g)
 
     // ---- K loop ---------------------------------------------------------------------------
     // T >= 2 tiles of 64 bytes.  The first H <= 2 of them hold the outlier range and are visited
-    // last, so the visiting order is H, H+1, .., T-1, 0, .., H-1.  Iterations 0 .. T-3 are the
-    // steady state (all of them normal tiles): wait for the tile, barrier, refill the stage read one
-    // iteration ago, 12 fragment reads, 16 MFMAs, and no branch but the loop's own.
+    // last: order H, H+1, .., T-1, 0, .., H-1.  Iteration `it` reads stage it % NSTAGE.
     const int T = g.kp / BKD;
     const int o_steps = DUAL ? g.n_off / 32 : 0;      // 32-byte k-steps of the outlier range (<= 4)
     const int H = (o_steps + 1) / 2;
     const int Tn = T - H;
     auto seq = [&](int it) { return it < Tn ? it + H : it - Tn; };
 
-    issue(seq(0), 0);
-    issue(seq(1), 1);
-    // park the scales in LDS (the compiler waits for exactly those loads; the tile loads stay in flight)
-    if (tid < BM) sx_lds[tid] = r_sx;
-    if (tid < BN) {
-        sn_lds[tid] = r_sn;
-        so_lds[tid] = r_so;
-        bs_lds[tid] = r_bs;
+#pragma unroll
+    for (int p = 0; p < AHEAD; ++p)
+        if (p < T) issue(seq(p), p);
+    // park the scales (the compiler waits for exactly those loads; the stage loads stay in flight)
+#pragma unroll
+    for (int u = 0; u < G::SPT; ++u) {
+        const int e = tid + u * G::THREADS;
+        if (e < G::NSCALE) sc_lds[e] = r_s[u];
     }
+
+    // The fragments of a stage's FIRST k-step are read one half-iteration early, under the MFMAs of
+    // the previous stage's second k-step; so the wait + barrier that makes stage it+1 visible sits in
+    // the middle of iteration it, and the refill of the stage read in iteration it-1 follows it.
+    //   iteration it:  read F1(it) | MFMA F0(it) | wait, barrier, refill | read F0(it+1) | MFMA F1(it)
+    if (AHEAD >= 3 && T >= 3) wait_vmcnt<2 * G::NLOAD>();
+    else wait_vmcnt<G::NLOAD>();
+    __builtin_amdgcn_s_barrier();
+    load_frags(smem, 0);
     int stage = 0;
-    for (int it = 0; it < T - 2; ++it) {
-        wait_vmcnt<NLOAD>();
-        __builtin_amdgcn_s_barrier();
-        issue(seq(it + 2), stage >= 1 ? stage - 1 : NSTAGE - 1);   // stage (it + 2) % 3
+    for (int it = 0; it < T - AHEAD; ++it) {     // steady state: every tile here is a normal tile
         const unsigned char *sb = smem + stage * STG;
-        load_frags(sb, 0);
+        const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
+        // Each fragment set is waited for explicitly BEFORE the next set's reads are issued (it was
+        // read a whole k-step ago, so the wait is free); the MFMAs below then need no wait of their
+        // own and the reads just issued land underneath them.
+        wait_lgkmcnt0();
         load_frags(sb, 1);
-        // keep all twelve reads ahead of the first MFMA: the second k-step's fragments then arrive
-        // under the first k-step's MFMAs instead of being re-serialised to save registers
         __builtin_amdgcn_sched_barrier(0);
         mma(0);
-        mma(1);
-        stage = stage + 1 == NSTAGE ? 0 : stage + 1;
-    }
-    // the last two tiles: nothing left to issue; either may be a head tile, of which only a
-    // trailing normal k-step (when the range boundary falls inside the tile) is summed here
-#pragma unroll 1
-    for (int it = T - 2; it < T; ++it) {
-        if (it + 1 < T) wait_vmcnt<NLOAD>();
-        else wait_vmcnt<0>();
+        __builtin_amdgcn_sched_barrier(0);       // the waits below must not float up into the MFMAs
+        wait_vmcnt<(AHEAD - 2) * G::NLOAD>();
         __builtin_amdgcn_s_barrier();
+        wait_lgkmcnt0();
+        load_frags(smem + nstage * STG, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(seq(it + AHEAD), stage >= 1 ? stage - 1 : NSTAGE - 1);   // stage (it + AHEAD) % NSTAGE
+        mma(1);
+        __builtin_amdgcn_sched_barrier(0);
+        stage = nstage;
+    }
+    // drain: the last AHEAD tiles, nothing left to issue; the head tiles are among them and only
+    // their trailing normal k-steps (when the range boundary falls inside a tile) are summed here
+#pragma unroll 1
+    for (int it = (T > AHEAD ? T - AHEAD : 0); it < T; ++it) {
         const unsigned char *sb = smem + stage * STG;
-        const int hs = it - Tn;   // >= 0: head tile number
-        if (hs < 0 || 2 * hs >= o_steps) {
-            load_frags(sb, 0);
-            mma(0);
+        const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
+        const int hs = it - Tn;                   // >= 0: head tile number
+        const bool use0 = hs < 0 || 2 * hs >= o_steps, use1 = hs < 0 || 2 * hs + 1 >= o_steps;
+        load_frags(sb, 1);
+        if (use0) mma(0);
+        if (it + 1 < T) {
+            if (AHEAD >= 3 && T - 2 - it >= 1) wait_vmcnt<G::NLOAD>();
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            load_frags(smem + nstage * STG, 0);
         }
-        if (hs < 0 || 2 * hs + 1 >= o_steps) {
-            load_frags(sb, 1);
-            mma(1);
-        }
-        stage = stage + 1 == NSTAGE ? 0 : stage + 1;
+        if (use1) mma(1);
+        stage = nstage;
     }
     wait_lgkmcnt0();                // this wave's scale writes have landed ...
-    __builtin_amdgcn_s_barrier();   // ... and everyone is done with the last normal tile's stage
+    __builtin_amdgcn_s_barrier();   // ... and everyone is done with every stage but the head tiles'
 
     // ---- epilogue -------------------------------------------------------------------------
-    // stage of iteration `it` is it % 3: head tile t sits in stage (Tn + t) % 3, the stage of the
-    // last normal tile (free now) is (Tn + 2) % 3 when H > 0; with H == 0 every stage is free.
-    const int free_stage = H > 0 ? (Tn + 2) % NSTAGE : 0;
-    unsigned char *patch = smem + (PATCH_IN_STAGE ? free_stage : NSTAGE) * STG + wave * PATCH_BYTES;
+    // head tile t sits in stage (Tn + t) % NSTAGE; the stages read just before them are free
+    int freeA = 0, freeB = 1;
+    if (H > 0) {
+        freeA = (Tn - 1 + 2 * NSTAGE) % NSTAGE;
+        freeB = (Tn - 2 + 2 * NSTAGE) % NSTAGE;
+    }
+    unsigned char *patch;
+    if constexpr (G::PATCH_ONE) patch = smem + freeA * STG + wave * PATCH_BYTES;
+    else if constexpr (G::PATCH_TWO) patch = smem + (wave < NW / 2 ? freeA : freeB) * STG + (wave % (NW / 2)) * PATCH_BYTES;
+    else patch = smem + NSTAGE * STG + wave * PATCH_BYTES;
+    (void)freeB;
     OutT *Y = reinterpret_cast<OutT *>(g.Y);
     constexpr int EPC = 16 / sizeof(OutT);          // output elements per 16-byte chunk
-    constexpr int NBP = sizeof(OutT) == 2 ? TN : 1; // 32-column blocks per patch pass
-    const bool dbg = g.dbg_n != nullptr || g.dbg_o != nullptr;
+    constexpr int NBP = sizeof(OutT) == 2 ? 2 : 1;  // 32-column blocks per patch pass (128 bytes per row)
 
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int ml = wm * WTM + i * 32 + frow;
+        const int ml = wm * G::WTM + i * 32 + frow;
         const int m_lane = m0 + ml;
         const float sx = sx_lds[ml];
 #pragma unroll
@@ -236,7 +291,7 @@ __global__ __launch_bounds__(TPB, 2) void gemm_dma_kernel(GemmArgs g)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int nl = j * 32 + 8 * q + 4 * fhalf;            // column inside the wave tile
-                    const int nt = wn * WTN + nl;                          // column inside the workgroup tile
+                    const int nt = wn * G::WTN + nl;                       // column inside the workgroup tile
                     const float4 sn = *reinterpret_cast<const float4 *>(sn_lds + nt);
                     const float4 so = *reinterpret_cast<const float4 *>(so_lds + nt);
                     const float4 bs = *reinterpret_cast<const float4 *>(bs_lds + nt);
@@ -250,7 +305,7 @@ __global__ __launch_bounds__(TPB, 2) void gemm_dma_kernel(GemmArgs g)
                         v = fmaf((float)acc[i][j][r], snv[e], v);
                         y[e] = fmaf(v, sx, bsv[e]);
                     }
-                    if (dbg) {
+                    if constexpr (DBG) {
                         const int n = n0 + nt;
                         if (m_lane < g.M && n + 4 <= g.N) {
 #pragma unroll
@@ -262,57 +317,61 @@ __global__ __launch_bounds__(TPB, 2) void gemm_dma_kernel(GemmArgs g)
                     }
                     if constexpr (sizeof(OutT) == 2) {
                         uint2 pk;
-                        pk.x = pack_bf16x2(y[0], y[1]);
-                        pk.y = pack_bf16x2(y[2], y[3]);
-                        *reinterpret_cast<uint2 *>(patch + frow * PATCH_RS + nl * 2) = pk;
+                        pk.x = cvt_pk_bf16(y[0], y[1]);
+                        pk.y = cvt_pk_bf16(y[2], y[3]);
+                        *reinterpret_cast<uint2 *>(patch + frow * PATCH_RS + (nl - jp * 32) * 2) = pk;
                     } else {
                         *reinterpret_cast<float4 *>(patch + frow * PATCH_RS + (nl - j * 32) * 4) = make_float4(y[0], y[1], y[2], y[3]);
                     }
                 }
             }
             // wave-private patch: 32 rows x 128 bytes -> 16-byte stores, 8 rows per instruction
-            const int n_patch0 = n0 + wn * WTN + (sizeof(OutT) == 2 ? 0 : jp * 32);
+            const int n_patch0 = n0 + wn * G::WTN + jp * 32;
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const int row = p * 8 + (lane >> 3), ch = lane & 7;
                 const uint4 v = *reinterpret_cast<const uint4 *>(patch + row * PATCH_RS + ch * 16);
-                const int m = m0 + wm * WTM + i * 32 + row;
+                const int m = m0 + wm * G::WTM + i * 32 + row;
                 const int n = n_patch0 + ch * EPC;
-                const bool col_ok = sizeof(OutT) == 2 ? (ch * EPC < WTN) : true;
-                if (m < g.M && n + EPC <= g.N && col_ok) *reinterpret_cast<uint4 *>(Y + (size_t)m * g.ldy + n) = v;
+                if (m < g.M && n + EPC <= g.N) *reinterpret_cast<uint4 *>(Y + (size_t)m * g.ldy + n) = v;
             }
         }
     }
 }
 
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool DBG, typename OutT>
+qarvd_status launch_one(const GemmArgs &g, hipStream_t st)
+{
+    using G = Geo<BM, BN, WM, WN, NSTAGE>;
+    auto k = gemm_dma_kernel<BM, BN, WM, WN, NSTAGE, DUAL, DBG, OutT>;
+    QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
+    hipLaunchKernelGGL(k, dim3(g.tiles_m * g.tiles_n), dim3(G::THREADS), G::LDS_BYTES, st, g);
+    return qarvd_launch_status();
+}
+
 }  // namespace
 
-template <int BM, int BN, bool DUAL>
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
 qarvd_status launch_dma(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
 {
     GemmArgs g = g0;
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
-    const size_t stg = (size_t)(BM + BN) * BKD;
-    const size_t lds = NSTAGE * stg + (4 * PATCH_BYTES <= stg ? 0 : 4 * PATCH_BYTES) + (BM + 3 * BN) * sizeof(float);
-    const int grid = g.tiles_m * g.tiles_n;
-    if (ydt == QARVD_BF16) {
-        auto k = gemm_dma_kernel<BM, BN, DUAL, uint16_t>;
-        QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(k, dim3(grid), dim3(TPB), lds, st, g);
-    } else {
-        auto k = gemm_dma_kernel<BM, BN, DUAL, float>;
-        QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(k, dim3(grid), dim3(TPB), lds, st, g);
-    }
-    return qarvd_launch_status();
+    const bool dbg = g.dbg_n != nullptr || g.dbg_o != nullptr;   // raw-accumulator dumps: separate, slower build
+    if (ydt == QARVD_BF16)
+        return dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, uint16_t>(g, st)
+                   : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, uint16_t>(g, st);
+    return dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, float>(g, st)
+               : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, float>(g, st);
 }
 
-template qarvd_status launch_dma<256, 128, true>(const GemmArgs &, qarvd_dtype, hipStream_t);
-template qarvd_status launch_dma<256, 128, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
-template qarvd_status launch_dma<192, 128, true>(const GemmArgs &, qarvd_dtype, hipStream_t);
-template qarvd_status launch_dma<192, 128, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
-template qarvd_status launch_dma<128, 128, true>(const GemmArgs &, qarvd_dtype, hipStream_t);
-template qarvd_status launch_dma<128, 128, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
+#define QARVD_INST(BM, BN, WM, WN, NS)                                                                      \
+    template qarvd_status launch_dma<BM, BN, WM, WN, NS, true>(const GemmArgs &, qarvd_dtype, hipStream_t); \
+    template qarvd_status launch_dma<BM, BN, WM, WN, NS, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
+QARVD_INST(256, 256, 2, 4, 4)
+QARVD_INST(256, 256, 2, 2, 4)
+QARVD_INST(256, 128, 2, 2, 3)
+QARVD_INST(192, 128, 2, 2, 3)
+QARVD_INST(128, 128, 2, 2, 4)
 
 }  // namespace qarvd_gemm
