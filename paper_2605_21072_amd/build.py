@@ -12,7 +12,8 @@ CSRC = PKG / "csrc"
 LIB = PKG / "libqarvd.so"
 SOURCES = ["quant_act.hip", "quantize_weight.hip", "gemm_api.hip", "gemm_staged.hip", "gemm_dma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = [
+import os as _os
+FLAGS = (["-DQARVD_PROF=1"] if _os.environ.get("QARVD_PROF") else []) + [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",                      # the epilogue and the detector spell out every fma
     "-fno-fast-math",

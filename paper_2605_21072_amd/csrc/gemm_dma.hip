@@ -37,6 +37,9 @@ namespace qarvd_gemm {
 
 namespace {
 
+#ifndef QARVD_PROF
+#define QARVD_PROF 0
+#endif
 constexpr int BKD = 64;                   // K bytes per stage row
 constexpr int PATCH_RS = 144;             // bytes per row of the output patch (128 + 16 pad)
 constexpr int PATCH_BYTES = 32 * PATCH_RS;
@@ -102,6 +105,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     float *sc_lds = reinterpret_cast<float *>(smem + G::SCALES_OFF);   // s_x[BM] | s_n[BN] | s_o[BN] | bias[BN]
     const float *sx_lds = sc_lds, *sn_lds = sc_lds + BM, *so_lds = sc_lds + BM + BN, *bs_lds = sc_lds + BM + 2 * BN;
 
+    const long long p_ts = QARVD_PROF ? clock64() : 0;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
@@ -207,6 +211,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     __builtin_amdgcn_s_barrier();
     load_frags(smem, 0);
     int stage = 0;
+    long long p_vm = 0, p_bar = 0, p_t0 = QARVD_PROF ? clock64() : 0;
     for (int it = 0; it < T - AHEAD; ++it) {     // steady state: every tile here is a normal tile
         const unsigned char *sb = smem + stage * STG;
         const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
@@ -218,8 +223,17 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
         __builtin_amdgcn_sched_barrier(0);
         mma(0);
         __builtin_amdgcn_sched_barrier(0);       // the waits below must not float up into the MFMAs
+#if QARVD_PROF
+        long long q0 = clock64();
+        wait_vmcnt<(AHEAD - 2) * G::NLOAD>();
+        long long q1 = clock64();
+        __builtin_amdgcn_s_barrier();
+        long long q2 = clock64();
+        p_vm += q1 - q0; p_bar += q2 - q1;
+#else
         wait_vmcnt<(AHEAD - 2) * G::NLOAD>();
         __builtin_amdgcn_s_barrier();
+#endif
         wait_lgkmcnt0();
         load_frags(smem + nstage * STG, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -247,6 +261,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
         if (use1) mma(1);
         stage = nstage;
     }
+    long long p_t1 = QARVD_PROF ? clock64() : 0;
     wait_lgkmcnt0();                // this wave's scale writes have landed ...
     __builtin_amdgcn_s_barrier();   // ... and everyone is done with every stage but the head tiles'
 
@@ -337,6 +352,14 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
             }
         }
     }
+#if QARVD_PROF
+    if (lane == 0) {
+        long long p_t2 = clock64();
+        int *o = (DBG && g.dbg_o) ? g.dbg_o + ((size_t)blockIdx.x * NW + wave) * 8
+                                  : reinterpret_cast<int *>(Y + (size_t)g.M * g.ldy) + ((size_t)blockIdx.x * NW + wave) * 8;
+        o[0] = (int)(p_t1 - p_t0); o[1] = (int)p_vm; o[2] = (int)p_bar; o[3] = (int)(p_t2 - p_t1); o[4] = T; o[5] = (int)(p_t0 & 0x7fffffff); o[6] = (int)(p_t2 & 0x7fffffff); o[7] = (int)(p_t0 - p_ts);
+    }
+#endif
 }
 
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool DBG, typename OutT>
