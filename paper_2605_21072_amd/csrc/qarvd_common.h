@@ -50,6 +50,21 @@ __device__ __forceinline__ int quantize_i8(float x, float s)
     return (int)r;
 }
 
+// Same result as quantize_i8, without the ~10-instruction IEEE division on the common path.
+//   y' = x * rcp(s) is within |x/s| * 2^-22 <= 127 * 2^-22 < 4e-5 of the true quotient (|x/s| <= 127
+//   under an absmax scale; larger quotients only occur with a static scale and are far from any
+//   boundary that matters or land in the slow path), and the oracle's RN(x/s) is within 8e-6 of it,
+//   so rint(y') == rint(RN(x/s)) whenever y' is at least 1e-4 away from a half-integer.  The few
+//   lanes closer than that (about 2 in 10^4) redo the exact division.  `r` must be rcp(s), s > 0.
+__device__ __forceinline__ int quantize_i8_fast(float x, float s, float r)
+{
+    const float y = x * r;
+    float q = rintf(y);
+    if (!(fabsf(y - q) < 0.4999f)) q = rintf(x / s);   // also taken for NaN / inf intermediates
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (int)q;
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // fp32 -> bf16 bits, round-to-nearest-even (finite inputs).

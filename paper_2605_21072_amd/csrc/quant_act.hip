@@ -47,44 +47,54 @@ struct ActArgs {
 };
 
 // Workgroup-wide max of a non-negative value; `red` holds one float per wave.
+template <int NWAVE = 4>
 __device__ __forceinline__ float block_max(float v, float *red)
 {
     v = wave_max(v);
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) red[wave] = v;
     __syncthreads();
-    float r = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float r = red[0];
+#pragma unroll
+    for (int w = 1; w < NWAVE; ++w) r = fmaxf(r, red[w]);
     return r;
 }
 
-// Register-resident rows: CH chunks of 4 channels per thread (K <= CH*1024, K % 4 == 0).
-// PosT is uint16_t when the packed extent fits, else uint32_t.
-template <typename T, typename PosT, int CH, bool STATIC>
-__global__ __launch_bounds__(TPB) void quant_act_rows_kernel(ActArgs a)
+// Register-resident rows: a workgroup of NT threads owns a token row at a time, CH chunks of 4
+// channels per thread (K <= CH*NT*4, K % 4 == 0).  IDENT: no permutation -- the quantized bytes
+// go straight from registers to memory (4 bytes per lane, contiguous over the wave) and no LDS
+// image or position table exists.  PosT is uint16_t when the packed extent fits, else uint32_t.
+template <typename T, typename PosT, int CH, int NT, bool STATIC, bool IDENT>
+__global__ __launch_bounds__(NT) void quant_act_rows_kernel(ActArgs a)
 {
+    constexpr int NWAVE = NT / 64;
     extern __shared__ __align__(16) unsigned char smem[];
-    // layout: qbuf[2][kp] | pos[K] | red[2][4]
+    // layout (permuted): qbuf[2][kp] | pos[K] | red[2][NWAVE];  (identity): red[2][NWAVE]
+    const size_t img_bytes = IDENT ? 0 : 2 * (size_t)a.kp;
+    const size_t pos_bytes = IDENT ? 0 : (((size_t)a.K * sizeof(PosT) + 15) & ~(size_t)15);
     int8_t *qbuf = reinterpret_cast<int8_t *>(smem);
-    PosT *pos = reinterpret_cast<PosT *>(smem + 2 * (size_t)a.kp);
-    float *red = reinterpret_cast<float *>(smem + 2 * (size_t)a.kp + (((size_t)a.K * sizeof(PosT) + 15) & ~(size_t)15));
+    PosT *pos = reinterpret_cast<PosT *>(smem + img_bytes);
+    float *red = reinterpret_cast<float *>(smem + img_bytes + pos_bytes);
     const int tid = threadIdx.x;
     const int K = a.K, kp = a.kp;
 
-    // channel -> packed position (a perm that is not a bijection gives undefined bytes, never an
-    // out-of-range LDS access: every entry starts at a valid position and bad indices are skipped)
-    if (a.perm) {
-        for (int k = tid; k < K; k += TPB) pos[k] = (PosT)a.n_off;
-        __syncthreads();
-        for (int p = tid; p < K; p += TPB) {
-            const int k = a.perm[p];
-            if ((unsigned)k < (unsigned)K) pos[k] = (PosT)(p < a.K_o ? p : a.n_off + (p - a.K_o));
+    if constexpr (!IDENT) {
+        // channel -> packed position (a perm that is not a bijection gives undefined bytes, never an
+        // out-of-range LDS access: every entry starts at a valid position and bad indices are skipped)
+        if (a.perm) {
+            for (int k = tid; k < K; k += NT) pos[k] = (PosT)a.n_off;
+            __syncthreads();
+            for (int p = tid; p < K; p += NT) {
+                const int k = a.perm[p];
+                if ((unsigned)k < (unsigned)K) pos[k] = (PosT)(p < a.K_o ? p : a.n_off + (p - a.K_o));
+            }
+        } else {
+            for (int k = tid; k < K; k += NT) pos[k] = (PosT)k;
         }
-    } else {
-        for (int k = tid; k < K; k += TPB) pos[k] = (PosT)k;
+        // zero both row images once: padding bytes are never overwritten afterwards
+        for (int i = tid; i < (2 * kp) / 16; i += NT) reinterpret_cast<uint4 *>(qbuf)[i] = make_uint4(0, 0, 0, 0);
+        __syncthreads();
     }
-    // zero both row images once: padding bytes are never overwritten afterwards
-    for (int i = tid; i < (2 * kp) / 16; i += TPB) reinterpret_cast<uint4 *>(qbuf)[i] = make_uint4(0, 0, 0, 0);
-    __syncthreads();
 
     const T *X = reinterpret_cast<const T *>(a.X);
     int buf = 0;
@@ -94,7 +104,7 @@ __global__ __launch_bounds__(TPB) void quant_act_rows_kernel(ActArgs a)
         float amax = 0.0f;
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
-            const int k = 4 * (tid + c * TPB);
+            const int k = 4 * (tid + c * NT);
             if (k < K) {
                 v[c] = Vec4Loader<T>::load(x + k);
                 amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[c].x), fabsf(v[c].y)), fmaxf(fabsf(v[c].z), fabsf(v[c].w))));
@@ -104,25 +114,119 @@ __global__ __launch_bounds__(TPB) void quant_act_rows_kernel(ActArgs a)
         if (STATIC) {
             s = a.static_scale;
         } else {
-            amax = block_max(amax, red + 4 * buf);
+            amax = block_max<NWAVE>(amax, red + NWAVE * buf);
             s = amax / 127.0f;
             if (tid == 0) a.s_x[m] = s;
         }
-        int8_t *q = qbuf + (size_t)buf * kp;
+        const bool zero = s == 0.0f;                       // all-zero token (or zero static scale): q = 0
+        const float r = __builtin_amdgcn_rcpf(s);
+        int8_t *out = a.Xq + (size_t)m * a.ldxq;
+        if constexpr (IDENT) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int k = 4 * (tid + c * NT);
+                if (k < kp) {                                // k >= K: zero padding up to the packed extent
+                    uint32_t w = 0;
+                    if (k < K && !zero) {
+                        w = (uint32_t)(quantize_i8_fast(v[c].x, s, r) & 255) | ((uint32_t)(quantize_i8_fast(v[c].y, s, r) & 255) << 8) |
+                            ((uint32_t)(quantize_i8_fast(v[c].z, s, r) & 255) << 16) | ((uint32_t)(quantize_i8_fast(v[c].w, s, r) & 255) << 24);
+                    }
+                    *reinterpret_cast<uint32_t *>(out + k) = w;
+                }
+            }
+        } else {
+            int8_t *q = qbuf + (size_t)buf * kp;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int k = 4 * (tid + c * NT);
+                if (k < K) {
+                    q[pos[k + 0]] = zero ? (int8_t)0 : (int8_t)quantize_i8_fast(v[c].x, s, r);
+                    q[pos[k + 1]] = zero ? (int8_t)0 : (int8_t)quantize_i8_fast(v[c].y, s, r);
+                    q[pos[k + 2]] = zero ? (int8_t)0 : (int8_t)quantize_i8_fast(v[c].z, s, r);
+                    q[pos[k + 3]] = zero ? (int8_t)0 : (int8_t)quantize_i8_fast(v[c].w, s, r);
+                }
+            }
+            __syncthreads();
+            for (int i = tid; i < kp / 16; i += NT)
+                reinterpret_cast<uint4 *>(out)[i] = reinterpret_cast<const uint4 *>(q)[i];
+        }
+    }
+}
+
+// Wave-per-row variant for short rows (K <= CH*256, K % 4 == 0): each of the four wavefronts of a
+// workgroup owns a token row at a time, so the absmax is a pure shuffle reduction, the packed row
+// image is wave-private and no workgroup barrier is needed after the position table is built.
+template <typename T, int CH, bool STATIC>
+__global__ __launch_bounds__(TPB) void quant_act_wave_kernel(ActArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    // layout: image[4][kp] | pos[K] (uint16)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int K = a.K, kp = a.kp;
+    int8_t *img = reinterpret_cast<int8_t *>(smem) + (size_t)wave * kp;
+    uint16_t *pos = reinterpret_cast<uint16_t *>(smem + 4 * (size_t)kp);
+    const T *X = reinterpret_cast<const T *>(a.X);
+    const int wave_id = blockIdx.x * 4 + wave, n_waves = gridDim.x * 4;
+
+    // the first row's loads go out before the position table is built: their memory latency and the
+    // table's (perm is read from cache) overlap
+    float4 v[CH];
+    auto load_row = [&](int m) {
+        const T *x = X + (size_t)m * a.ldx;
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
-            const int k = 4 * (tid + c * TPB);
+            const int k = 4 * (lane + c * 64);
+            if (k < K) v[c] = Vec4Loader<T>::load(x + k);
+        }
+    };
+    int m = wave_id;
+    if (m < a.M) load_row(m);
+
+    if (a.perm) {
+        for (int k = tid; k < K; k += TPB) pos[k] = (uint16_t)a.n_off;
+        __syncthreads();
+        for (int p = tid; p < K; p += TPB) {
+            const int k = a.perm[p];
+            if ((unsigned)k < (unsigned)K) pos[k] = (uint16_t)(p < a.K_o ? p : a.n_off + (p - a.K_o));
+        }
+    } else {
+        for (int k = tid; k < K; k += TPB) pos[k] = (uint16_t)k;
+    }
+    for (int i = tid; i < (4 * kp) / 16; i += TPB) reinterpret_cast<uint4 *>(smem)[i] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+
+    for (; m < a.M; m += n_waves) {
+        float amax = 0.0f;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int k = 4 * (lane + c * 64);
+            if (k < K) amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[c].x), fabsf(v[c].y)), fmaxf(fabsf(v[c].z), fabsf(v[c].w))));
+        }
+        float s;
+        if (STATIC) {
+            s = a.static_scale;
+        } else {
+            amax = wave_max(amax);
+            s = amax / 127.0f;
+            if (lane == 0) a.s_x[m] = s;
+        }
+        const bool zero = s == 0.0f;
+        const float r = __builtin_amdgcn_rcpf(s);
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int k = 4 * (lane + c * 64);
             if (k < K) {
-                q[pos[k + 0]] = (int8_t)quantize_i8(v[c].x, s);
-                q[pos[k + 1]] = (int8_t)quantize_i8(v[c].y, s);
-                q[pos[k + 2]] = (int8_t)quantize_i8(v[c].z, s);
-                q[pos[k + 3]] = (int8_t)quantize_i8(v[c].w, s);
+                img[pos[k + 0]] = zero ? (int8_t)0 : (int8_t)quantize_i8_fast(v[c].x, s, r);
+                img[pos[k + 1]] = zero ? (int8_t)0 : (int8_t)quantize_i8_fast(v[c].y, s, r);
+                img[pos[k + 2]] = zero ? (int8_t)0 : (int8_t)quantize_i8_fast(v[c].z, s, r);
+                img[pos[k + 3]] = zero ? (int8_t)0 : (int8_t)quantize_i8_fast(v[c].w, s, r);
             }
         }
-        __syncthreads();
+        if (m + n_waves < a.M) load_row(m + n_waves);     // next row in flight during the copy-out
+        // the image is private to this wave and LDS operations of one wave complete in order
         int8_t *out = a.Xq + (size_t)m * a.ldxq;
-        for (int i = tid; i < kp / 16; i += TPB)
-            reinterpret_cast<uint4 *>(out)[i] = reinterpret_cast<const uint4 *>(q)[i];
+        for (int i = lane; i < kp / 16; i += 64)
+            reinterpret_cast<uint4 *>(out)[i] = reinterpret_cast<const uint4 *>(img)[i];
     }
 }
 
@@ -178,17 +282,40 @@ int num_cu()
 
 constexpr size_t LDS_LIMIT = 160 * 1024;
 
-template <typename T, typename PosT, int CH, bool STATIC>
-qarvd_status launch_rows(const ActArgs &a, hipStream_t st)
+template <typename T, typename PosT, int CH, int NT, bool STATIC, bool IDENT>
+qarvd_status launch_rows_one(const ActArgs &a, hipStream_t st)
 {
-    const size_t lds = 2 * (size_t)a.kp + (((size_t)a.K * sizeof(PosT) + 15) & ~(size_t)15) + 8 * sizeof(float);
-    auto kern = quant_act_rows_kernel<T, PosT, CH, STATIC>;
+    const size_t lds = (IDENT ? 0 : 2 * (size_t)a.kp + (((size_t)a.K * sizeof(PosT) + 15) & ~(size_t)15)) + 2 * (NT / 64) * sizeof(float);
+    auto kern = quant_act_rows_kernel<T, PosT, CH, NT, STATIC, IDENT>;
     if (lds > 64 * 1024)
         QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    int occ = (int)(LDS_LIMIT / (lds < 1024 ? 1024 : lds));
+    const int occ_threads = 2048 / NT;
+    occ = occ < 1 ? 1 : (occ > occ_threads ? occ_threads : occ);
+    int grid = num_cu() * occ;
+    if (grid > a.M) grid = a.M;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, a);
+    return qarvd_launch_status();
+}
+
+template <typename T, typename PosT, int CH, int NT, bool STATIC>
+qarvd_status launch_rows(const ActArgs &a, hipStream_t st)
+{
+    // no permutation and a packed extent that whole 4-byte words cover: straight register -> memory path
+    if (!a.perm && a.kp <= CH * NT * 4) return launch_rows_one<T, PosT, CH, NT, STATIC, true>(a, st);
+    return launch_rows_one<T, PosT, CH, NT, STATIC, false>(a, st);
+}
+
+template <typename T, int CH, bool STATIC>
+qarvd_status launch_wave(const ActArgs &a, hipStream_t st)
+{
+    const size_t lds = 4 * (size_t)a.kp + (((size_t)a.K * 2 + 15) & ~(size_t)15);
+    auto kern = quant_act_wave_kernel<T, CH, STATIC>;
     int occ = (int)(LDS_LIMIT / lds);
     occ = occ < 1 ? 1 : (occ > 8 ? 8 : occ);
     int grid = num_cu() * occ;
-    if (grid > a.M) grid = a.M;
+    const int need = (a.M + 3) / 4;
+    if (grid > need) grid = need;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(TPB), lds, st, a);
     return qarvd_launch_status();
 }
@@ -198,11 +325,13 @@ qarvd_status dispatch(const ActArgs &a, hipStream_t st)
 {
     const bool vec_ok = (a.K % 4 == 0) && (a.ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.X) % (4 * sizeof(T))) == 0);
     const size_t lds16 = 2 * (size_t)a.kp + (size_t)a.K * 2 + 64;
-    if (vec_ok && a.kp <= 65535 && a.K <= 14 * 1024 && lds16 <= LDS_LIMIT) {
-        if (a.K <= 2 * 1024) return launch_rows<T, uint16_t, 2, STATIC>(a, st);
-        if (a.K <= 5 * 1024) return launch_rows<T, uint16_t, 5, STATIC>(a, st);
-        if (a.K <= 9 * 1024) return launch_rows<T, uint16_t, 9, STATIC>(a, st);
-        return launch_rows<T, uint16_t, 14, STATIC>(a, st);
+    if (vec_ok && a.kp <= 65535 && a.K <= 16 * 1024 && lds16 <= LDS_LIMIT) {
+        if (a.perm && a.K <= 6 * 256) return launch_wave<T, 6, STATIC>(a, st);
+        if (a.perm && a.K <= 12 * 256) return launch_wave<T, 12, STATIC>(a, st);
+        if (!a.perm && a.K <= 5 * 1024) return launch_rows<T, uint16_t, 5, 256, STATIC>(a, st);
+        if (a.K <= 6 * 1024) return launch_rows<T, uint16_t, 3, 512, STATIC>(a, st);
+        if (a.K <= 10 * 1024) return launch_rows<T, uint16_t, 5, 512, STATIC>(a, st);
+        return launch_rows<T, uint16_t, 4, 1024, STATIC>(a, st);
     }
     int grid = a.M < num_cu() * 8 ? a.M : num_cu() * 8;
     hipLaunchKernelGGL((quant_act_generic_kernel<T, STATIC>), dim3(grid), dim3(TPB), 0, st, a);

@@ -115,6 +115,35 @@ def test_quant_act_parity(M, K, c, dtype):
     assert np.array_equal(logical(Xq_g, K, K_o), Xq_o)
 
 
+@pytest.mark.parametrize("K,amax", [(1536, 100.3), (8960, 3.7), (1000, 127.0), (250, 0.011)])
+def test_quant_act_rounding_boundaries(K, amax):
+    """Values sitting on and next to the half-integer rounding boundaries of x / s: the kernel's
+    reciprocal shortcut must fall back to the exact division exactly where it matters."""
+    rng = np.random.default_rng(K)
+    M = 16
+    s64 = np.float64(np.float32(np.float32(amax) / np.float32(127.0)))
+    X = np.empty((M, K), np.float32)
+    for m in range(M):
+        k = rng.integers(-126, 127, K).astype(np.float64) + 0.5
+        x = (k * s64).astype(np.float32)
+        steps = rng.integers(-3, 4, K)
+        for _ in range(3):
+            x = np.where(steps > 0, np.nextafter(x, np.float32(np.inf)), np.where(steps < 0, np.nextafter(x, np.float32(-np.inf)), x))
+            steps = steps - np.sign(steps)
+        X[m] = x
+        X[m, rng.integers(0, K)] = np.float32(amax)        # fixes the token's absmax
+    sel = (rng.random(K) < 0.02).astype(np.uint8)
+    perm, K_o = oracle.build_perm(sel)
+    Xq_o, sx_o = oracle.quant_act(X, perm)
+    Xq_g, sx_g = q.quant_act(dev(X), dev(perm) if K_o else None, K_o)
+    torch.cuda.synchronize()
+    assert np.array_equal(sx_g.cpu().numpy().view(np.uint32), sx_o.view(np.uint32))
+    assert np.array_equal(logical(Xq_g, K, K_o), Xq_o)
+    Xq_s = q.quant_act_static(dev(X), dev(perm) if K_o else None, K_o, float(s64) * 0.5)   # clip fires
+    torch.cuda.synchronize()
+    assert np.array_equal(logical(Xq_s, K, K_o), oracle.quant_act_static(X, np.float32(s64 * 0.5), perm))
+
+
 def test_quant_act_strided_input_and_output():
     rng = np.random.default_rng(5)
     M, K = 21, 1536
