@@ -196,6 +196,13 @@ def main():
                                    round(float(np.mean([x["speedup_gemm_vs_bf16"] for x in t])), 3),
                                    speedup_linear_vs_bf16=None if args.no_bf16 else
                                    round(float(np.mean([x["speedup_linear_vs_bf16"] for x in t])), 3))
+    try:
+        issue_peak = q.probe_mfma_peak(20000)
+        out["mfma_issue_peak"] = dict(tops=round(issue_peak, 1), frac_of_datasheet=round(issue_peak / PEAK_INT8_TOPS, 4),
+                                      gemm_frac_of_issue_peak=round(achieved / issue_peak, 4),
+                                      note="register-resident v_mfma_i32_32x32x32_i8 loop on every CU, measured in this run")
+    except Exception as e:  # diagnostic only
+        out["mfma_issue_peak"] = dict(error=str(e))
     out["paper_context"] = "paper reports 1.30x end-to-end INT8 speedup and 1.97x size reduction on an NVIDIA A6000 " \
                            "with Triton kernels (whole pipeline, not this kernel)"
 

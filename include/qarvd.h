@@ -122,7 +122,8 @@ qarvd_status qarvd_quantize_weight(const float *W, int32_t N, int32_t K, int64_t
  *   X     in   [M, ldx] of `xdt` (QARVD_F32 or QARVD_BF16; bf16 is widened exactly first)
  *   perm  in   i32 [K] or NULL (identity; K_o must then be 0)
  *   Xq    out  i8 [M, ldxq] packed for (K, K_o);  s_x out f32 [M]
- * Fully asynchronous on `stream`.  X must be 16-byte aligned with ldx*sizeof(elem) % 16 == 0.
+ * Fully asynchronous on `stream`.  The register-resident kernels need K % 4 == 0, ldx % 4 == 0, a
+ * 16-byte (fp32) / 8-byte (bf16) aligned X and K <= 16384; anything else runs a slower general kernel.
  */
 qarvd_status qarvd_quant_act(const void *X, qarvd_dtype xdt, int32_t M, int32_t K, int64_t ldx,
                              const int32_t *perm, int32_t K_o, int8_t *Xq, int64_t ldxq,
@@ -170,6 +171,18 @@ qarvd_status qarvd_w8a8_dual_gemm_variant(int32_t variant, const int8_t *Xq, int
                                           void *stream);
 int32_t qarvd_gemm_num_variants(void);
 const char *qarvd_gemm_variant_name(int32_t variant);
+
+/*
+ * Diagnostic for reports (not part of the layer): the measured issue-bound INT8 MFMA rate of the
+ * current device, in TOPS.  Runs a register-resident loop of `iters` x 8 v_mfma_i32_32x32x32_i8
+ * per wavefront on every CU (two wavefronts per SIMD) and times it with HIP events on `stream`.
+ *   workspace  device, >= 4160 bytes, 4-byte aligned (operand seeds)
+ *   tops_host  HOST out
+ * Synchronises `stream`.  The result is below the datasheet figure when the MFMA clock is
+ * power-limited; benchmark reports quote the GEMM against both.
+ */
+qarvd_status qarvd_probe_mfma_peak(int32_t iters, void *workspace, size_t workspace_bytes,
+                                   double *tops_host, void *stream);
 
 #ifdef __cplusplus
 }

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     load_library,
     packed_k,
     packed_normal_offset,
+    probe_mfma_peak,
     quant_act,
     quant_act_static,
     quantize_weight,

@@ -73,6 +73,8 @@ def load_library():
     lib.qarvd_gemm_num_variants.restype = i32
     lib.qarvd_gemm_variant_name.argtypes = [i32]
     lib.qarvd_gemm_variant_name.restype = C.c_char_p
+    lib.qarvd_probe_mfma_peak.argtypes = [i32, vp, C.c_size_t, C.POINTER(C.c_double), vp]
+    lib.qarvd_probe_mfma_peak.restype = C.c_int
     _lib = lib
     return lib
 
@@ -123,6 +125,15 @@ def gemm_num_variants() -> int:
 
 def gemm_variant_name(i: int) -> str:
     return load_library().qarvd_gemm_variant_name(i).decode()
+
+
+def probe_mfma_peak(iters: int = 20000, stream=None) -> float:
+    """qarvd_probe_mfma_peak: measured issue-bound INT8 MFMA rate of the current device in TOPS."""
+    lib = load_library()
+    ws = torch.empty(8192, dtype=torch.uint8, device="cuda")
+    tops = C.c_double(0.0)
+    _check(lib.qarvd_probe_mfma_peak(int(iters), _ptr(ws), ws.numel(), C.byref(tops), _stream(stream)), "qarvd_probe_mfma_peak")
+    return float(tops.value)
 
 
 @dataclass

@@ -10,7 +10,7 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libqarvd.so"
-SOURCES = ["quant_act.hip", "quantize_weight.hip", "gemm_api.hip", "gemm_staged.hip", "gemm_dma.hip"]
+SOURCES = ["quant_act.hip", "quantize_weight.hip", "gemm_api.hip", "gemm_staged.hip", "gemm_dma.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 import os as _os
 FLAGS = (["-DQARVD_PROF=1"] if _os.environ.get("QARVD_PROF") else []) + [

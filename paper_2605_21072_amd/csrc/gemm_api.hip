@@ -38,24 +38,29 @@ bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)
     return true;
 }
 
-// Heuristic: LDS-direct kernels when the shape allows them; the tile height that wastes the fewest
-// MFMA cycles on the last partial wave of tiles over the chip's 256 CUs (two workgroups each).
+// Heuristic.  Measured on MI355X the MFMA loop of every LDS-direct variant runs at about the same
+// chip-wide rate (the INT8 MFMA clock is power-limited), so what separates them is how many
+// "rounds" of tiles the busiest CU sees: cost = rounds x tile area x workgroups sharing a CU.
+// Ties go to the larger tile (half the L1/L2 operand traffic per MAC); the three-stage four-wave
+// tiles carry a penalty because only one stage can be in flight behind the one being read.
 int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
 {
     const bool dual = g.n_off > 0;
     if (g.n_off <= 128 && vector_out_ok(g, ydt)) {
-        const int cand[3] = {dual ? 5 : 6, dual ? 7 : 8, dual ? 9 : 10};
-        const int bm[3] = {256, 192, 128};
-        int best = cand[0];
+        struct Cand { int variant, bm, bn, wg_per_cu; double penalty; };
+        const Cand cand[4] = {{dual ? 11 : 12, 256, 256, 1, 1.00},
+                              {dual ? 9 : 10, 128, 128, 2, 1.02},
+                              {dual ? 5 : 6, 256, 128, 2, 1.12},
+                              {dual ? 7 : 8, 192, 128, 2, 1.12}};
+        int best = cand[0].variant;
         double best_cost = 1e300;
-        for (int c = 0; c < 3; ++c) {
-            const long tiles = (long)((g.M + bm[c] - 1) / bm[c]) * ((g.N + 127) / 128);
-            const long rounds = (tiles + 255) / 256;             // tiles per CU, busiest CU
-            double cost = (double)rounds * bm[c];                 // MFMA time of the busiest CU
-            cost *= 1.0 + 16.0 / bm[c];                           // smaller tiles re-read operands more often
+        for (const Cand &c : cand) {
+            const long tiles = (long)((g.M + c.bm - 1) / c.bm) * ((g.N + c.bn - 1) / c.bn);
+            const long rounds = (tiles + 256L * c.wg_per_cu - 1) / (256L * c.wg_per_cu);
+            const double cost = (double)rounds * c.wg_per_cu * c.bm * c.bn * c.penalty;
             if (cost < best_cost) {
                 best_cost = cost;
-                best = cand[c];
+                best = c.variant;
             }
         }
         return best;

@@ -33,6 +33,8 @@
 //     pieces covering whole 128-byte row segments.
 #include "gemm_common.h"
 
+#include <type_traits>
+
 namespace qarvd_gemm {
 
 namespace {
@@ -280,7 +282,12 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     OutT *Y = reinterpret_cast<OutT *>(g.Y);
     constexpr int EPC = 16 / sizeof(OutT);          // output elements per 16-byte chunk
     constexpr int NBP = sizeof(OutT) == 2 ? 2 : 1;  // 32-column blocks per patch pass (128 bytes per row)
+    const bool has_o = DUAL && o_steps > 0;
 
+    // the whole epilogue exists twice: with the outlier sum (HASO) and without it (a layer with no
+    // outlier channels run through the dual kernel, or the single-accumulator build)
+    auto epilogue = [&](auto haso_tag) {
+        constexpr bool HASO = decltype(haso_tag)::value;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int ml = wm * G::WTM + i * 32 + frow;
@@ -292,15 +299,20 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
             for (int jj = 0; jj < NBP; ++jj) {
                 const int j = jp + jj;
                 v16i ao;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) ao[r] = 0;
-                if constexpr (DUAL) {
-                    for (int s = 0; s < o_steps; ++s) {
-                        const unsigned char *hb = smem + ((Tn + (s >> 1)) % NSTAGE) * STG;
-                        const int c = coff[s & 1];
-                        const v4i wo = *reinterpret_cast<const v4i *>(hb + w_base + j * 32 * BKD + c);
-                        const v4i xo = *reinterpret_cast<const v4i *>(hb + x_base + i * 32 * BKD + c);
-                        ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(wo, xo, ao, 0, 0, 0);
+                {
+                    if constexpr (HASO) {   // first outlier k-step starts from a zero accumulator, the rest chain on it
+                        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                        const unsigned char *hb0 = smem + (Tn % NSTAGE) * STG;
+                        ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                            *reinterpret_cast<const v4i *>(hb0 + w_base + j * 32 * BKD + coff[0]),
+                            *reinterpret_cast<const v4i *>(hb0 + x_base + i * 32 * BKD + coff[0]), zero, 0, 0, 0);
+                        for (int s = 1; s < o_steps; ++s) {
+                            const unsigned char *hb = smem + ((Tn + (s >> 1)) % NSTAGE) * STG;
+                            const int c = coff[s & 1];
+                            const v4i wo = *reinterpret_cast<const v4i *>(hb + w_base + j * 32 * BKD + c);
+                            const v4i xo = *reinterpret_cast<const v4i *>(hb + x_base + i * 32 * BKD + c);
+                            ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(wo, xo, ao, 0, 0, 0);
+                        }
                     }
                 }
 #pragma unroll
@@ -316,8 +328,14 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int r = 4 * q + e;
-                        float v = (float)ao[r] * sov[e];
-                        v = fmaf((float)acc[i][j][r], snv[e], v);
+                        float v;
+                        if constexpr (HASO) {
+                            v = (float)ao[r] * sov[e];
+                            v = fmaf((float)acc[i][j][r], snv[e], v);
+                        } else {
+                            // acc_o == 0: (float)0 * s_o is +0 and the first fma reduces to this one
+                            v = fmaf((float)acc[i][j][r], snv[e], 0.0f);
+                        }
                         y[e] = fmaf(v, sx, bsv[e]);
                     }
                     if constexpr (DBG) {
@@ -326,7 +344,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 if (g.dbg_n) g.dbg_n[(size_t)m_lane * g.N + n + e] = acc[i][j][4 * q + e];
-                                if (g.dbg_o) g.dbg_o[(size_t)m_lane * g.N + n + e] = ao[4 * q + e];
+                                if (g.dbg_o) g.dbg_o[(size_t)m_lane * g.N + n + e] = HASO ? ao[4 * q + e] : 0;
                             }
                         }
                     }
@@ -351,6 +369,13 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
                 if (m < g.M && n + EPC <= g.N) *reinterpret_cast<uint4 *>(Y + (size_t)m * g.ldy + n) = v;
             }
         }
+    }
+    };
+    if constexpr (DUAL) {
+        if (has_o) epilogue(std::true_type{});
+        else epilogue(std::false_type{});
+    } else {
+        epilogue(std::false_type{});
     }
 #if QARVD_PROF
     if (lane == 0) {
