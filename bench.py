@@ -167,15 +167,31 @@ def main():
     s0 = layers[dom[0]]["spec"]
     dom_ops = 2.0 * s0.macs
     achieved = dom_ops / dom_us / 1e6
-    roofline = dict(bound="mfma", kernel="qarvd_w8a8_dual_gemm M=%d K=%d N=%d" % (s0.M, s0.K, s0.N),
+    # HBM-side bytes per launch come from committed rocprofv3 counter runs (bench.py cannot run the profiler)
+    traffic_db = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic_config2.json")) as fh:
+            traffic_db = json.load(fh)
+    except OSError:
+        pass
+
+    def traffic_of(kernel):
+        t = traffic_db.get(kernel)
+        return None if t is None else t["fetch_bytes"] + t["write_bytes"]
+
+    dom_kernel = "qarvd_w8a8_dual_gemm M=%d K=%d N=%d" % (s0.M, s0.K, s0.N)
+    roofline = dict(bound="mfma", kernel=dom_kernel,
                     achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TOP/s",
-                    frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=None, avg_launch_us=round(dom_us, 2))
+                    frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=traffic_of(dom_kernel),
+                    algorithmic_ops=dom_ops, avg_launch_us=round(dom_us, 2))
     # the memory-bound kernel of the path
     qi = int(np.argmax(quant_us))
     sq = layers[qi]["spec"]
-    quant_roof = dict(bound="hbm", kernel="qarvd_quant_act M=%d K=%d" % (sq.M, sq.K),
+    q_kernel = "qarvd_quant_act M=%d K=%d" % (sq.M, sq.K)
+    quant_roof = dict(bound="hbm", kernel=q_kernel,
                       achieved=per_layer[qi]["quant_gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
-                      frac=round(per_layer[qi]["quant_gbs"] / PEAK_HBM_GBS, 4), avg_launch_us=per_layer[qi]["quant_us"])
+                      frac=round(per_layer[qi]["quant_gbs"] / PEAK_HBM_GBS, 4), traffic=traffic_of(q_kernel),
+                      algorithmic_bytes=5.0 * sq.M * sq.K + 4.0 * sq.M, avg_launch_us=per_layer[qi]["quant_us"])
 
     out = dict(metric="INT8 TOPS of the dual-scale W8A8 linear (quant_act + dual GEMM); % of dense INT8 MFMA peak; "
                       "speedup vs bf16",
