@@ -303,8 +303,12 @@ def test_determinism_byte_identical_reruns():
     assert torch.equal(a[4], b[4]) and torch.equal(a[5], b[5]) and torch.equal(a[0].Wq, b[0].Wq)
 
 
-FULL_SIZE = ["cfg2.q.c4", "cfg2.ffn_up.c16", "cfg2.ffn_down.c64", "cfg2.o.c0", "cfg4.M520.ffn_down.c32",
-             "cfg4.M1560.ffn_up.c0", "cfg5.q.c128", "cfg5.ffn_down.c32", "cfg3.b29.ffn_down", "cfg3.b14.cross_k"]
+def _full_size_names():
+    """Every layer of configs 2, 3 (all 30 blocks x 10 linears), 4 and 5."""
+    return [s.name for cfg in (2, 3, 4, 5) for s in wl.config_layers(cfg)]
+
+
+FULL_SIZE = _full_size_names()
 
 
 @pytest.mark.parametrize("name", FULL_SIZE)
