@@ -27,8 +27,9 @@ constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 bool vector_out_ok(const GemmArgs &g, qarvd_dtype ydt)
 {
     const size_t esz = ydt == QARVD_F32 ? 4 : 2;
+    // the LDS-direct kernels also address a tile's rows with 32-bit byte offsets: 256 rows x stride < 2^31
     return (g.N % 8) == 0 && qarvd_aligned16(g.Y) && ((g.ldy * esz) % 16) == 0 && qarvd_aligned16(g.s_n) &&
-           qarvd_aligned16(g.s_o) && qarvd_aligned16(g.bias);
+           qarvd_aligned16(g.s_o) && qarvd_aligned16(g.bias) && g.ldxq <= (1 << 22) && g.ldwq <= (1 << 22);
 }
 
 bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)

@@ -64,6 +64,20 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 }
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14)); }
 
+// One LDS-direct load: lane l moves the 16 bytes at base + voffset(l) + soffset to lds + 16*l (lds and
+// soffset wave-uniform).  The buffer descriptor (raw, no stride, no bounds) is rebuilt from `base` at
+// each call; it is wave-uniform, so the compiler keeps it in four SGPRs across the K loop.  The body
+// exists in the device pass only: the host pass has neither the descriptor type nor the builtin.
+__device__ __forceinline__ void buffer_load_lds16(const void *base, int voffset, int soffset, unsigned char *lds)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7fffffff, 0x00020000);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, QARVD_LPTR(lds), 16, voffset, soffset, 0, 0);
+#else
+    (void)base; (void)voffset; (void)soffset; (void)lds;
+#endif
+}
+
 // two fp32 -> packed bf16, round-to-nearest-even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b)
 {
@@ -108,6 +122,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     const float *sx_lds = sc_lds, *sn_lds = sc_lds + BM, *so_lds = sc_lds + BM + BN, *bs_lds = sc_lds + BM + 2 * BN;
 
     const long long p_ts = QARVD_PROF ? clock64() : 0;
+    const long long p_rs = QARVD_PROF ? wall_clock64() : 0;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
@@ -134,24 +149,28 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     // (l & 3) of row (l >> 2) with global chunk (l & 3) ^ swz64(l >> 2).
     const int drow = lane >> 2;
     const int dchunk = ((lane & 3) ^ swz64(drow)) << 4;
-    const int8_t *pa[NA];
-    const int8_t *pb[NB];
+    // Buffer addressing: a tile-relative base in SGPRs, a constant 32-bit byte offset per lane and the
+    // K position as the scalar offset, so the K loop spends no vector ALU work on addresses.  Rows
+    // past the matrix are clamped to its last row (their products land in rows/columns never stored).
+    const int8_t *const base_a = g.Xq + (size_t)m0 * g.ldxq;
+    const int8_t *const base_b = g.Wq + (size_t)n0 * g.ldwq;
+    int va[NA], vb[NB];
 #pragma unroll
     for (int i = 0; i < NA; ++i)
-        pa[i] = g.Xq + (size_t)min(m0 + (NW * i + wave) * 16 + drow, g.M - 1) * g.ldxq + dchunk;
+        va[i] = (min(m0 + (NW * i + wave) * 16 + drow, g.M - 1) - m0) * (int)g.ldxq + dchunk;
 #pragma unroll
     for (int i = 0; i < NB; ++i)
-        pb[i] = g.Wq + (size_t)min(n0 + (NW * i + wave) * 16 + drow, g.N - 1) * g.ldwq + dchunk;
+        vb[i] = (min(n0 + (NW * i + wave) * 16 + drow, g.N - 1) - n0) * (int)g.ldwq + dchunk;
 
     auto issue = [&](int tile, int stage) {
         unsigned char *sb = smem + stage * STG;
-        const size_t koff = (size_t)tile * BKD;
+        const int koff = tile * BKD;
 #pragma unroll
         for (int i = 0; i < NA; ++i)
-            __builtin_amdgcn_global_load_lds(QARVD_GPTR(pa[i] + koff), QARVD_LPTR(sb + (NW * i + wave) * 1024), 16, 0, 0);
+            buffer_load_lds16(base_a, va[i], koff, sb + (NW * i + wave) * 1024);
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            __builtin_amdgcn_global_load_lds(QARVD_GPTR(pb[i] + koff), QARVD_LPTR(sb + BM * BKD + (NW * i + wave) * 1024), 16, 0, 0);
+            buffer_load_lds16(base_b, vb[i], koff, sb + BM * BKD + (NW * i + wave) * 1024);
     };
 
     // ---- fragment addressing --------------------------------------------------------------
@@ -183,6 +202,32 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks][j], xf[ks][i], acc[i][j], 0, 0, 0);
+    };
+
+    // Instruction-order hints for the scheduler (masks: 0x008 MFMA, 0x100 LDS read, 0x020 VMEM read):
+    // one fragment read after each of the first TM+TN MFMAs, and in the second half-iteration the
+    // LDS-direct loads spread over the following MFMAs.
+    auto interleave_reads = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM * TN; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+    };
+    // Second half of an iteration: the TM+TN fragment reads, then the NLOAD refill loads (the
+    // loads write LDS, so they cannot move ahead of the reads), spread evenly over the MFMAs.
+    auto interleave_reads_and_loads = [&]() {
+        constexpr int S = TM * TN, R = TM + TN, OPS = R + G::NLOAD;
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+#pragma unroll
+            for (int j = 0; j < OPS; ++j)
+                if (j * S / OPS == i) {
+                    if (j < R) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
+        }
     };
 
     // ---- K loop ---------------------------------------------------------------------------
@@ -221,9 +266,10 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
         // read a whole k-step ago, so the wait is free); the MFMAs below then need no wait of their
         // own and the reads just issued land underneath them.
         wait_lgkmcnt0();
-        load_frags(sb, 1);
         __builtin_amdgcn_sched_barrier(0);
+        load_frags(sb, 1);
         mma(0);
+        interleave_reads();                      // MFMA, read, MFMA, read, ...: the MFMA pipe never drains
         __builtin_amdgcn_sched_barrier(0);       // the waits below must not float up into the MFMAs
 #if QARVD_PROF
         long long q0 = clock64();
@@ -237,10 +283,11 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
         __builtin_amdgcn_s_barrier();
 #endif
         wait_lgkmcnt0();
-        load_frags(smem + nstage * STG, 0);
         __builtin_amdgcn_sched_barrier(0);
+        load_frags(smem + nstage * STG, 0);
         issue(seq(it + AHEAD), stage >= 1 ? stage - 1 : NSTAGE - 1);   // stage (it + AHEAD) % NSTAGE
         mma(1);
+        interleave_reads_and_loads();
         __builtin_amdgcn_sched_barrier(0);
         stage = nstage;
     }
@@ -382,7 +429,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
         long long p_t2 = clock64();
         int *o = (DBG && g.dbg_o) ? g.dbg_o + ((size_t)blockIdx.x * NW + wave) * 8
                                   : reinterpret_cast<int *>(Y + (size_t)g.M * g.ldy) + ((size_t)blockIdx.x * NW + wave) * 8;
-        o[0] = (int)(p_t1 - p_t0); o[1] = (int)p_vm; o[2] = (int)p_bar; o[3] = (int)(p_t2 - p_t1); o[4] = T; o[5] = (int)(p_t0 & 0x7fffffff); o[6] = (int)(p_t2 & 0x7fffffff); o[7] = (int)(p_t0 - p_ts);
+        o[0] = (int)(p_t1 - p_t0); o[1] = (int)p_vm; o[2] = (int)p_bar; o[3] = (int)(p_t2 - p_t1); o[4] = (int)(wall_clock64() - p_rs); o[5] = (int)(p_t0 & 0x7fffffff); o[6] = (int)(p_t2 & 0x7fffffff); o[7] = (int)(p_t0 - p_ts);
     }
 #endif
 }
@@ -407,10 +454,10 @@ qarvd_status launch_dma(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     g.tiles_n = (g.N + BN - 1) / BN;
     const bool dbg = g.dbg_n != nullptr || g.dbg_o != nullptr;   // raw-accumulator dumps: separate, slower build
     if (ydt == QARVD_BF16)
-        return dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, uint16_t>(g, st)
-                   : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, uint16_t>(g, st);
-    return dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, float>(g, st)
-               : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, float>(g, st);
+        return !dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, uint16_t>(g, st)
+                    : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, uint16_t>(g, st);
+    return !dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, float>(g, st)
+                : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, float>(g, st);
 }
 
 #define QARVD_INST(BM, BN, WM, WN, NS)                                                                      \
