@@ -19,8 +19,6 @@ const Variant kVariants[] = {
     {"lds-direct 128x128 (4 waves, 4 stages) single", 128, 128, 0, true, launch_dma<128, 128, 2, 2, 4, false>},
     {"lds-direct 256x256 (8 waves, 4 stages) dual", 256, 256, 128, true, launch_dma<256, 256, 2, 4, 4, true>},
     {"lds-direct 256x256 (8 waves, 4 stages) single", 256, 256, 0, true, launch_dma<256, 256, 2, 4, 4, false>},
-    {"lds-direct 256x256 (4 waves of 128x128, 4 stages) dual", 256, 256, 128, true, launch_dma<256, 256, 2, 2, 4, true>},
-    {"lds-direct 256x256 (4 waves of 128x128, 4 stages) single", 256, 256, 0, true, launch_dma<256, 256, 2, 2, 4, false>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 

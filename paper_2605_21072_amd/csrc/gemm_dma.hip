@@ -11,26 +11,34 @@
 // four-wave tiles, two workgroups per CU.
 //
 // Data path
-//   * global -> LDS with global_load_lds_dwordx4, no VGPR staging.  One instruction fills 1 KB of
-//     LDS contiguously (16 rows x 64 B); the XOR swizzle that keeps the 32-row fragment reads off
-//     the same banks is applied on the GLOBAL side: the lane that fills slot s of row r fetches
+//   * persistent workgroups: the grid is as many workgroups as the chip holds at once and each walks
+//     the tile list with that stride.  The LDS stages form one ring across tiles, so the first
+//     stages of the next tile are issued before the epilogue of the current one starts and land
+//     under it; its scales travel in registers during the K loop and sit in a second LDS buffer.
+//   * global -> LDS with buffer_load_dwordx4 ... lds, no VGPR staging: tile base in SGPRs, one
+//     constant byte offset per lane, the K position as scalar offset.  One instruction fills 1 KB
+//     of LDS contiguously (16 rows x 64 B); the XOR swizzle that keeps the 32-row fragment reads
+//     off the same banks is applied on the GLOBAL side: the lane that fills slot s of row r fetches
 //     16-byte chunk s ^ swz64(r) of that row.  Measured load-to-use latency of these loads is
 //     0.7 us from L2 and 1-1.4 us from memory, so NSTAGE-1 stages are kept in flight.
 //   * explicit waits: s_waitcnt vmcnt(n) for the stage about to be read, then a bare s_barrier
 //     (a fence would drain every outstanding load), then the refill of the stage everybody
-//     finished reading one iteration ago.  The steady-state loop is a single basic block.
+//     finished reading one iteration ago.  The steady-state loop is a single basic block in which
+//     fragment reads and refill loads alternate with the MFMAs (sched_group_barrier).
 //   * W fragment = MFMA A operand, X fragment = B operand, so a lane owns ONE token row and four
 //     consecutive output features per register quad: the per-token scale is a per-lane scalar, the
-//     per-feature scales and bias are float4 LDS reads, four results pack into one 8-byte write.
+//     per-feature scales and bias are 16-byte LDS reads, four results pack into one 8-byte write.
 //   * only the normal-range sum lives in registers through the K loop.  The (at most two)
 //     64-byte tiles holding the outlier range are visited LAST and stay resident in LDS; the
 //     epilogue sums each 32 x 32 block's outlier k-steps into a 16-register temporary (1-4
 //     MFMAs) and merges the two INT32 accumulators as
 //         r = (float)acc_o * s_o;  r = fmaf((float)acc_n, s_n, r);  y = fmaf(r, s_x, bias).
-//   * scales and bias are parked in LDS at kernel start; bf16 results are packed with
-//     v_cvt_pk_bf16_f32 (round-to-nearest-even), transposed through a wave-private LDS patch
-//     (row stride 144 B: conflict-free 8-byte writes and 16-byte reads) and stored as 16-byte
-//     pieces covering whole 128-byte row segments.
+//   * bf16 results are packed with v_cvt_pk_bf16_f32 (round-to-nearest-even), transposed through a
+//     wave-private swizzled LDS patch (32 rows x 64 B) and stored as 16-byte chunks, 16 rows x 64 B
+//     per instruction.  The epilogue waits for the prefetched stages once, before its first store,
+//     so that no stage wait of the next tile has output stores ahead of it in the memory counter.
+#include <algorithm>
+
 #include "gemm_common.h"
 
 #include <type_traits>
@@ -43,13 +51,21 @@ namespace {
 #define QARVD_PROF 0
 #endif
 constexpr int BKD = 64;                   // K bytes per stage row
-constexpr int PATCH_RS = 144;             // bytes per row of the output patch (128 + 16 pad)
+// Output patch of a wave: 32 rows x 64 bytes (one 32x32 block of bf16, half a block of fp32), the
+// four 16-byte chunks of row r stored at chunk positions c ^ ((r >> 2) & 3) so that neither the
+// accumulator-layout writes nor the row-layout reads pile up on LDS banks.
+constexpr int PATCH_RS = 64;
 constexpr int PATCH_BYTES = 32 * PATCH_RS;
 
 #define QARVD_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define QARVD_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 typedef float v2f __attribute__((ext_vector_type(2)));
+// LDS is read and written through these native vector types only: accesses typed with the HIP
+// float4 / uint4 structs make the compiler drain every LDS-direct load in flight (s_waitcnt vmcnt(0))
+// before them, which would serialise the next tile's prefetch with the epilogue.
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 
 // Swizzle for 64-byte LDS rows (four 16-byte slots): any 8 consecutive rows spread over all
@@ -95,14 +111,12 @@ struct Geo {
     static constexpr int NA = BM / 16 / NW, NB = BN / 16 / NW;   // LDS-direct loads per wave per stage
     static constexpr int NLOAD = NA + NB;
     static constexpr int STG = (BM + BN) * BKD;
-    static constexpr int PATCHES = NW * PATCH_BYTES;
+    static constexpr int PATCHES = NW * PATCH_BYTES;   // all of them fit into the one stage read last before the head tiles
     // where the output patches go: inside one free stage, split over two free stages, or behind the stages
-    static constexpr bool PATCH_ONE = PATCHES <= STG;
-    static constexpr bool PATCH_TWO = !PATCH_ONE && NSTAGE >= 4 && PATCHES <= 2 * STG && (NW % 2) == 0;
-    static constexpr int PATCH_EXTRA = (PATCH_ONE || PATCH_TWO) ? 0 : PATCHES;
-    static constexpr int SCALES_OFF = NSTAGE * STG + PATCH_EXTRA;
+    static_assert(PATCHES <= STG, "the output patches share one free stage");
+    static constexpr int SCALES_OFF = NSTAGE * STG;
     static constexpr int NSCALE = BM + 3 * BN;
-    static constexpr int LDS_BYTES = SCALES_OFF + NSCALE * (int)sizeof(float);
+    static constexpr int LDS_BYTES = SCALES_OFF + 2 * NSCALE * (int)sizeof(float);   // two scale buffers: tile t uses buffer t & 1
     static constexpr int SPT = (NSCALE + THREADS - 1) / THREADS;   // scale values per thread
     static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "row groups must divide over the waves");
     static_assert(WTM % 32 == 0 && WTN % 64 == 0, "wave tile is TM x TN blocks, TN even (a patch pass holds 64 bf16 columns)");
@@ -118,59 +132,76 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     constexpr int TM = G::TM, TN = G::TN, NA = G::NA, NB = G::NB, NW = G::NW, STG = G::STG;
     constexpr int AHEAD = NSTAGE - 1;                  // stages in flight
     extern __shared__ __align__(16) unsigned char smem[];
-    float *sc_lds = reinterpret_cast<float *>(smem + G::SCALES_OFF);   // s_x[BM] | s_n[BN] | s_o[BN] | bias[BN]
-    const float *sx_lds = sc_lds, *sn_lds = sc_lds + BM, *so_lds = sc_lds + BM + BN, *bs_lds = sc_lds + BM + 2 * BN;
+    float *const sc_both = reinterpret_cast<float *>(smem + G::SCALES_OFF);   // 2 x { s_x[BM] | s_n[BN] | s_o[BN] | bias[BN] }
 
     const long long p_ts = QARVD_PROF ? clock64() : 0;
     const long long p_rs = QARVD_PROF ? wall_clock64() : 0;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    int tm, tn;
-    tile_coords(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+    // ---- persistent workgroup: tiles blockIdx.x, blockIdx.x + gridDim.x, ... ------------------
+    // (m0, n0) is the tile being computed; the load addressing below may already point at the next one.
+    const int ntiles = g.tiles_m * g.tiles_n;
+    int tile = blockIdx.x;
+    int m0, n0;
 
-    // ---- scales and bias of this tile: global -> registers now, -> LDS once the first stage
-    // loads are in flight (so the latencies overlap); read back by the epilogue --------------
-    float r_s[G::SPT];
-#pragma unroll
-    for (int u = 0; u < G::SPT; ++u) {
-        const int e = tid + u * G::THREADS;
-        float v = 0.f;
-        if (e < BM) v = g.s_x[min(m0 + e, g.M - 1)];
-        else if (e < BM + BN) v = g.s_n[min(n0 + e - BM, g.N - 1)];
-        else if (e < BM + 2 * BN) v = g.s_o[min(n0 + e - BM - BN, g.N - 1)];
-        else if (e < BM + 3 * BN && g.bias) v = g.bias[min(n0 + e - BM - 2 * BN, g.N - 1)];
-        r_s[u] = v;
-    }
-
-    // ---- LDS-direct load addressing -------------------------------------------------------
-    // Load i of this wave fills rows (NW*i + wave)*16 .. +16 of the operand tile; lane l fills slot
-    // (l & 3) of row (l >> 2) with global chunk (l & 3) ^ swz64(l >> 2).
-    const int drow = lane >> 2;
-    const int dchunk = ((lane & 3) ^ swz64(drow)) << 4;
+    // LDS-direct load addressing.  Load i of this wave fills rows (NW*i + wave)*16 .. +16 of the
+    // operand tile; lane l fills slot (l & 3) of row (l >> 2) with global chunk (l & 3) ^ swz64(l >> 2).
     // Buffer addressing: a tile-relative base in SGPRs, a constant 32-bit byte offset per lane and the
     // K position as the scalar offset, so the K loop spends no vector ALU work on addresses.  Rows
     // past the matrix are clamped to its last row (their products land in rows/columns never stored).
-    const int8_t *const base_a = g.Xq + (size_t)m0 * g.ldxq;
-    const int8_t *const base_b = g.Wq + (size_t)n0 * g.ldwq;
+    const int drow = lane >> 2;
+    const int dchunk = ((lane & 3) ^ swz64(drow)) << 4;
+    const int8_t *base_a, *base_b;
     int va[NA], vb[NB];
+    int lm0, ln0;                                   // tile the load addressing points at
+    auto aim_loads = [&](int t) {
+        int tm, tn;
+        tile_coords(t, g.tiles_m, g.tiles_n, tm, tn);
+        lm0 = tm * BM;
+        ln0 = tn * BN;
+        base_a = g.Xq + (size_t)lm0 * g.ldxq;
+        base_b = g.Wq + (size_t)ln0 * g.ldwq;
 #pragma unroll
-    for (int i = 0; i < NA; ++i)
-        va[i] = (min(m0 + (NW * i + wave) * 16 + drow, g.M - 1) - m0) * (int)g.ldxq + dchunk;
+        for (int i = 0; i < NA; ++i)
+            va[i] = (min(lm0 + (NW * i + wave) * 16 + drow, g.M - 1) - lm0) * (int)g.ldxq + dchunk;
 #pragma unroll
-    for (int i = 0; i < NB; ++i)
-        vb[i] = (min(n0 + (NW * i + wave) * 16 + drow, g.N - 1) - n0) * (int)g.ldwq + dchunk;
-
-    auto issue = [&](int tile, int stage) {
+        for (int i = 0; i < NB; ++i)
+            vb[i] = (min(ln0 + (NW * i + wave) * 16 + drow, g.N - 1) - ln0) * (int)g.ldwq + dchunk;
+    };
+    auto issue = [&](int ktile, int stage) {
         unsigned char *sb = smem + stage * STG;
-        const int koff = tile * BKD;
+        const int koff = ktile * BKD;
 #pragma unroll
         for (int i = 0; i < NA; ++i)
             buffer_load_lds16(base_a, va[i], koff, sb + (NW * i + wave) * 1024);
 #pragma unroll
         for (int i = 0; i < NB; ++i)
             buffer_load_lds16(base_b, vb[i], koff, sb + BM * BKD + (NW * i + wave) * 1024);
+    };
+
+    // Scales and bias of a tile: global -> registers while the PREVIOUS tile's K loop runs, ->
+    // the other LDS buffer when that loop is done; read back by the tile's own epilogue.
+    float r_s[G::SPT];
+    auto fetch_scales = [&](int sm0, int sn0) {
+#pragma unroll
+        for (int u = 0; u < G::SPT; ++u) {
+            const int e = tid + u * G::THREADS;
+            float v = 0.f;
+            if (e < BM) v = g.s_x[min(sm0 + e, g.M - 1)];
+            else if (e < BM + BN) v = g.s_n[min(sn0 + e - BM, g.N - 1)];
+            else if (e < BM + 2 * BN) v = g.s_o[min(sn0 + e - BM - BN, g.N - 1)];
+            else if (e < BM + 3 * BN && g.bias) v = g.bias[min(sn0 + e - BM - 2 * BN, g.N - 1)];
+            r_s[u] = v;
+        }
+    };
+    auto park_scales = [&](int buf) {
+        float *dst = sc_both + buf * G::NSCALE;
+#pragma unroll
+        for (int u = 0; u < G::SPT; ++u) {
+            const int e = tid + u * G::THREADS;
+            if (e < G::NSCALE) dst[e] = r_s[u];
+        }
     };
 
     // ---- fragment addressing --------------------------------------------------------------
@@ -182,13 +213,6 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     coff[1] = ((2 | fhalf) ^ fsw) << 4;
 
     v16i acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-
     v4i xf[2][TM], wf[2][TN];   // fragments of the two k-steps of a stage
     auto load_frags = [&](const unsigned char *sb, int ks) {
 #pragma unroll
@@ -239,26 +263,64 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     const int Tn = T - H;
     auto seq = [&](int it) { return it < Tn ? it + H : it - Tn; };
 
+    // Stages form a ring that runs on across tiles: K tile `it` of a tile whose first K tile sits in
+    // stage `base` uses stage (base + it) % NSTAGE, and the next tile starts at (base + T) % NSTAGE.
+    int base = 0, sbuf = 0;
+    const int PF = min(min(NSTAGE - H - 1, AHEAD), T);   // next-tile stages that fit beside the heads and the patch stage
+    bool first_stage_landed = false, rest_pending = false;
+    aim_loads(tile);
+    fetch_scales(lm0, ln0);
+    issue(seq(0), 0);
+    issue(seq(1), 1);   // T >= 2; a fixed number of loads, so the wait the compiler puts before the
+    park_scales(0);     // scale writes covers exactly the scale fetch and leaves the stage loads in flight
 #pragma unroll
-    for (int p = 0; p < AHEAD; ++p)
+    for (int p = 2; p < AHEAD; ++p)
         if (p < T) issue(seq(p), p);
-    // park the scales (the compiler waits for exactly those loads; the stage loads stay in flight)
+    // The scales of the tile after the current one travel in registers while the current K loop runs.
+    // They are fetched and parked on every pass, for the last tile too (it re-reads its own), so that
+    // each fetch is followed by its use on every path and the compiler never has to drain the stage
+    // loads to protect these registers.
+    auto fetch_next_scales = [&](int t) {
+        int tm, tn;
+        tile_coords(min(t, ntiles - 1), g.tiles_m, g.tiles_n, tm, tn);
+        fetch_scales(tm * BM, tn * BN);
+    };
+    long long p_vm = 0, p_bar = 0, p_loop = 0, p_epi = 0, p_pro = 0, p_mark = p_ts;
+    int p_tiles = 0;
+
+    for (;;) {
+    m0 = lm0;
+    n0 = ln0;
+    const int next_tile = tile + (int)gridDim.x;
+    const bool more = next_tile < ntiles;
 #pragma unroll
-    for (int u = 0; u < G::SPT; ++u) {
-        const int e = tid + u * G::THREADS;
-        if (e < G::NSCALE) sc_lds[e] = r_s[u];
-    }
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
     // The fragments of a stage's FIRST k-step are read one half-iteration early, under the MFMAs of
     // the previous stage's second k-step; so the wait + barrier that makes stage it+1 visible sits in
     // the middle of iteration it, and the refill of the stage read in iteration it-1 follows it.
     //   iteration it:  read F1(it) | MFMA F0(it) | wait, barrier, refill | read F0(it+1) | MFMA F1(it)
-    if (AHEAD >= 3 && T >= 3) wait_vmcnt<2 * G::NLOAD>();
-    else wait_vmcnt<G::NLOAD>();
-    __builtin_amdgcn_s_barrier();
-    load_frags(smem, 0);
-    int stage = 0;
-    long long p_vm = 0, p_bar = 0, p_t0 = QARVD_PROF ? clock64() : 0;
+    // The wait counts assume only stage loads are outstanding; the previous tile's output stores may
+    // still be, but they are older than every load issued after them, so the waits only get stricter.
+    // A tile whose first stage was prefetched during the previous epilogue needs no wait at all here:
+    // that epilogue waited for the prefetch before its first store.
+    if (!first_stage_landed) {
+        if (AHEAD >= 3 && T >= 3) wait_vmcnt<2 * G::NLOAD>();
+        else wait_vmcnt<G::NLOAD>();
+    }
+    __builtin_amdgcn_s_barrier();   // first stage visible; everyone has left the previous tile's epilogue
+    fetch_next_scales(next_tile);   // so its patch and head stages and the other scale buffer can be reused
+    if (rest_pending) {             // (fetch before the stage loads: the waits count those from the youngest)
+        for (int p = PF; p < AHEAD; ++p)
+            if (p < T) issue(seq(p), (base + p) % NSTAGE);
+    }
+    load_frags(smem + base * STG, 0);
+    int stage = base;
+    long long p_t0 = QARVD_PROF ? clock64() : 0;
     for (int it = 0; it < T - AHEAD; ++it) {     // steady state: every tile here is a normal tile
         const unsigned char *sb = smem + stage * STG;
         const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
@@ -277,7 +339,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
         long long q1 = clock64();
         __builtin_amdgcn_s_barrier();
         long long q2 = clock64();
-        p_vm += q1 - q0; p_bar += q2 - q1;
+        p_bar += q2 - q1; (void)q0;
 #else
         wait_vmcnt<(AHEAD - 2) * G::NLOAD>();
         __builtin_amdgcn_s_barrier();
@@ -315,20 +377,33 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     __builtin_amdgcn_s_barrier();   // ... and everyone is done with every stage but the head tiles'
 
     // ---- epilogue -------------------------------------------------------------------------
-    // head tile t sits in stage (Tn + t) % NSTAGE; the stages read just before them are free
-    int freeA = 0, freeB = 1;
-    if (H > 0) {
-        freeA = (Tn - 1 + 2 * NSTAGE) % NSTAGE;
-        freeB = (Tn - 2 + 2 * NSTAGE) % NSTAGE;
+    // head tile t sits in stage (base + Tn + t) % NSTAGE; the stage read just before the heads takes
+    // the output patches; whatever is left of the ring is free for the next tile already.
+    const int freeA = (base + Tn - 1 + 2 * NSTAGE) % NSTAGE;
+    const int hstage0 = (base + Tn) % NSTAGE;
+    const int nbase = (base + T) % NSTAGE;
+    park_scales(sbuf ^ 1);          // free since the previous tile's epilogue; nothing else is in flight here
+    if (more) {
+        aim_loads(next_tile);
+        for (int p = 0; p < PF; ++p) issue(seq(p), (nbase + p) % NSTAGE);
     }
-    unsigned char *patch;
-    if constexpr (G::PATCH_ONE) patch = smem + freeA * STG + wave * PATCH_BYTES;
-    else if constexpr (G::PATCH_TWO) patch = smem + (wave < NW / 2 ? freeA : freeB) * STG + (wave % (NW / 2)) * PATCH_BYTES;
-    else patch = smem + NSTAGE * STG + wave * PATCH_BYTES;
-    (void)freeB;
+    const float *sc_lds = sc_both + sbuf * G::NSCALE;
+    const float *sx_lds = sc_lds, *sn_lds = sc_lds + BM, *so_lds = sc_lds + BM + BN, *bs_lds = sc_lds + BM + 2 * BN;
+    unsigned char *const patch = smem + freeA * STG + wave * PATCH_BYTES;
     OutT *Y = reinterpret_cast<OutT *>(g.Y);
     constexpr int EPC = 16 / sizeof(OutT);          // output elements per 16-byte chunk
-    constexpr int NBP = sizeof(OutT) == 2 ? 2 : 1;  // 32-column blocks per patch pass (128 bytes per row)
+    const int pswz = (frow >> 2) & 3;               // chunk swizzle of this lane's patch row when writing
+    // patch -> global: 16 rows x 64 bytes per instruction, rows of the tile that exist only
+    auto flush_patch = [&](int i, int ncol0) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int row = p * 16 + (lane >> 2), ch = lane & 3;
+            const v4i v = *reinterpret_cast<const v4i *>(patch + row * PATCH_RS + ((ch ^ ((row >> 2) & 3)) << 4));
+            const int m = m0 + wm * G::WTM + i * 32 + row;
+            const int n = ncol0 + ch * EPC;
+            if (m < g.M && n + EPC <= g.N) *reinterpret_cast<v4i *>(Y + (size_t)m * g.ldy + n) = v;
+        }
+    };
     const bool has_o = DUAL && o_steps > 0;
 
     // the whole epilogue exists twice: with the outlier sum (HASO) and without it (a layer with no
@@ -341,20 +416,18 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
         const int m_lane = m0 + ml;
         const float sx = sx_lds[ml];
 #pragma unroll
-        for (int jp = 0; jp < TN; jp += NBP) {
-#pragma unroll
-            for (int jj = 0; jj < NBP; ++jj) {
-                const int j = jp + jj;
+        for (int j = 0; j < TN; ++j) {
+            {
                 v16i ao;
                 {
                     if constexpr (HASO) {   // first outlier k-step starts from a zero accumulator, the rest chain on it
                         const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                        const unsigned char *hb0 = smem + (Tn % NSTAGE) * STG;
+                        const unsigned char *hb0 = smem + hstage0 * STG;
                         ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(
                             *reinterpret_cast<const v4i *>(hb0 + w_base + j * 32 * BKD + coff[0]),
                             *reinterpret_cast<const v4i *>(hb0 + x_base + i * 32 * BKD + coff[0]), zero, 0, 0, 0);
                         for (int s = 1; s < o_steps; ++s) {
-                            const unsigned char *hb = smem + ((Tn + (s >> 1)) % NSTAGE) * STG;
+                            const unsigned char *hb = smem + ((hstage0 + (s >> 1)) % NSTAGE) * STG;
                             const int c = coff[s & 1];
                             const v4i wo = *reinterpret_cast<const v4i *>(hb + w_base + j * 32 * BKD + c);
                             const v4i xo = *reinterpret_cast<const v4i *>(hb + x_base + i * 32 * BKD + c);
@@ -366,9 +439,9 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
                 for (int q = 0; q < 4; ++q) {
                     const int nl = j * 32 + 8 * q + 4 * fhalf;            // column inside the wave tile
                     const int nt = wn * G::WTN + nl;                       // column inside the workgroup tile
-                    const float4 sn = *reinterpret_cast<const float4 *>(sn_lds + nt);
-                    const float4 so = *reinterpret_cast<const float4 *>(so_lds + nt);
-                    const float4 bs = *reinterpret_cast<const float4 *>(bs_lds + nt);
+                    const v4f sn = *reinterpret_cast<const v4f *>(sn_lds + nt);
+                    const v4f so = *reinterpret_cast<const v4f *>(so_lds + nt);
+                    const v4f bs = *reinterpret_cast<const v4f *>(bs_lds + nt);
                     float y[4];
                     const float snv[4] = {sn.x, sn.y, sn.z, sn.w}, sov[4] = {so.x, so.y, so.z, so.w};
                     const float bsv[4] = {bs.x, bs.y, bs.z, bs.w};
@@ -395,26 +468,28 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
                             }
                         }
                     }
+                    if (i == 0 && j == 0 && q == 0) {
+                        // The next tile's first stages were issued when this epilogue began and have had its
+                        // first block's arithmetic to land.  Waiting for them here, before the first output
+                        // store is issued, means no later wait for a stage load ever has an output store ahead
+                        // of it in the (in-order) memory counter.
+                        __builtin_amdgcn_sched_barrier(0);
+                        wait_vmcnt<0>();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                     if constexpr (sizeof(OutT) == 2) {
-                        uint2 pk;
+                        v2u pk;
                         pk.x = cvt_pk_bf16(y[0], y[1]);
                         pk.y = cvt_pk_bf16(y[2], y[3]);
-                        *reinterpret_cast<uint2 *>(patch + frow * PATCH_RS + (nl - jp * 32) * 2) = pk;
+                        *reinterpret_cast<v2u *>(patch + frow * PATCH_RS + ((q ^ pswz) << 4) + 8 * fhalf) = pk;
                     } else {
-                        *reinterpret_cast<float4 *>(patch + frow * PATCH_RS + (nl - j * 32) * 4) = make_float4(y[0], y[1], y[2], y[3]);
+                        const int c = 2 * (q & 1) + fhalf;
+                        *reinterpret_cast<v4f *>(patch + frow * PATCH_RS + ((c ^ pswz) << 4)) = v4f{y[0], y[1], y[2], y[3]};
+                        if (q & 1) flush_patch(i, n0 + wn * G::WTN + j * 32 + (q >> 1) * 16);
                     }
                 }
             }
-            // wave-private patch: 32 rows x 128 bytes -> 16-byte stores, 8 rows per instruction
-            const int n_patch0 = n0 + wn * G::WTN + jp * 32;
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int row = p * 8 + (lane >> 3), ch = lane & 7;
-                const uint4 v = *reinterpret_cast<const uint4 *>(patch + row * PATCH_RS + ch * 16);
-                const int m = m0 + wm * G::WTM + i * 32 + row;
-                const int n = n_patch0 + ch * EPC;
-                if (m < g.M && n + EPC <= g.N) *reinterpret_cast<uint4 *>(Y + (size_t)m * g.ldy + n) = v;
-            }
+            if constexpr (sizeof(OutT) == 2) flush_patch(i, n0 + wn * G::WTN + j * 32);
         }
     }
     };
@@ -425,11 +500,26 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
         epilogue(std::false_type{});
     }
 #if QARVD_PROF
-    if (lane == 0) {
-        long long p_t2 = clock64();
+    {
+        const long long p_t2 = clock64();
+        if (p_tiles == 0) p_vm = p_t0 - p_mark; else p_pro += p_t0 - p_mark;
+        p_loop += p_t1 - p_t0; p_epi += p_t2 - p_t1; p_mark = p_t2; ++p_tiles;
+    }
+#endif
+    if (!more) break;
+    first_stage_landed = PF >= 1;
+    rest_pending = true;
+    base = nbase;
+    sbuf ^= 1;
+    tile = next_tile;
+    }
+#if QARVD_PROF
+    if (lane == 0) {   // per wave: sums over its tiles of loop, load-wait, barrier-wait, epilogue, lead-in ticks
+        OutT *Yp = reinterpret_cast<OutT *>(g.Y);
         int *o = (DBG && g.dbg_o) ? g.dbg_o + ((size_t)blockIdx.x * NW + wave) * 8
-                                  : reinterpret_cast<int *>(Y + (size_t)g.M * g.ldy) + ((size_t)blockIdx.x * NW + wave) * 8;
-        o[0] = (int)(p_t1 - p_t0); o[1] = (int)p_vm; o[2] = (int)p_bar; o[3] = (int)(p_t2 - p_t1); o[4] = (int)(wall_clock64() - p_rs); o[5] = (int)(p_t0 & 0x7fffffff); o[6] = (int)(p_t2 & 0x7fffffff); o[7] = (int)(p_t0 - p_ts);
+                                  : reinterpret_cast<int *>(Yp + (size_t)g.M * g.ldy) + ((size_t)blockIdx.x * NW + wave) * 8;
+        o[0] = (int)p_loop; o[1] = (int)p_vm; o[2] = (int)p_bar; o[3] = (int)p_epi; o[4] = (int)(wall_clock64() - p_rs);
+        o[5] = p_tiles; o[6] = (int)(clock64() - p_ts); o[7] = (int)p_pro;
     }
 #endif
 }
@@ -440,7 +530,20 @@ qarvd_status launch_one(const GemmArgs &g, hipStream_t st)
     using G = Geo<BM, BN, WM, WN, NSTAGE>;
     auto k = gemm_dma_kernel<BM, BN, WM, WN, NSTAGE, DUAL, DBG, OutT>;
     QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
-    hipLaunchKernelGGL(k, dim3(g.tiles_m * g.tiles_n), dim3(G::THREADS), G::LDS_BYTES, st, g);
+    // persistent grid: as many workgroups as the chip holds at once, each walking the tile list with that stride
+    int dev = 0;
+    QARVD_HIP_TRY(hipGetDevice(&dev));
+    static int cu_count[64] = {0};              // per device, filled on first use (same value from any thread)
+    int cus = (dev >= 0 && dev < 64) ? cu_count[dev] : 0;
+    if (cus <= 0) {
+        QARVD_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        if (dev >= 0 && dev < 64) cu_count[dev] = cus;
+    }
+    constexpr int LDS_PER_CU = 160 * 1024;
+    const int wg_per_cu = std::max(1, std::min(LDS_PER_CU / G::LDS_BYTES, (G::WAVES_PER_EU * 4) / G::NW));
+    const int slots = std::max(8, cus * wg_per_cu / 8 * 8);      // a multiple of the XCD count keeps a workgroup's tiles on one XCD
+    const int grid = std::min(g.tiles_m * g.tiles_n, slots);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(G::THREADS), G::LDS_BYTES, st, g);
     return qarvd_launch_status();
 }
 
@@ -464,7 +567,6 @@ qarvd_status launch_dma(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     template qarvd_status launch_dma<BM, BN, WM, WN, NS, true>(const GemmArgs &, qarvd_dtype, hipStream_t); \
     template qarvd_status launch_dma<BM, BN, WM, WN, NS, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
 QARVD_INST(256, 256, 2, 4, 4)
-QARVD_INST(256, 256, 2, 2, 4)
 QARVD_INST(256, 128, 2, 2, 3)
 QARVD_INST(192, 128, 2, 2, 3)
 QARVD_INST(128, 128, 2, 2, 4)
