@@ -10,10 +10,10 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libqarvd.so"
-SOURCES = ["quant_act.hip", "quantize_weight.hip", "gemm_api.hip", "gemm_staged.hip", "gemm_dma.hip", "probe.hip"]
+SOURCES = ["quant_act.hip", "quantize_weight.hip", "gemm_api.hip", "gemm_staged.hip", "gemm_dma.hip", "gemm_mfma16.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-import os as _os
-FLAGS = (["-DQARVD_PROF=1"] if _os.environ.get("QARVD_PROF") else []) + [
+# QARVD_PROF=1 in the environment compiles the GEMM kernels with their per-wave tick counters
+FLAGS = (["-DQARVD_PROF=" + os.environ["QARVD_PROF"]] if os.environ.get("QARVD_PROF") else []) + [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",                      # the epilogue and the detector spell out every fma
     "-fno-fast-math",

@@ -19,15 +19,17 @@ const Variant kVariants[] = {
     {"lds-direct 128x128 (4 waves, 4 stages) single", 128, 128, 0, true, launch_dma<128, 128, 2, 2, 4, false>},
     {"lds-direct 256x256 (8 waves, 4 stages) dual", 256, 256, 128, true, launch_dma<256, 256, 2, 4, 4, true>},
     {"lds-direct 256x256 (8 waves, 4 stages) single", 256, 256, 0, true, launch_dma<256, 256, 2, 4, 4, false>},
+    {"16x16x64 256x224 (8 waves, 4 stages) dual", 256, 224, 128, true, launch_mfma16<256, 224, 4, 2, 4, true>},
+    {"16x16x64 256x224 (8 waves, 4 stages) single", 256, 224, 0, true, launch_mfma16<256, 224, 4, 2, 4, false>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 bool vector_out_ok(const GemmArgs &g, qarvd_dtype ydt)
 {
     const size_t esz = ydt == QARVD_F32 ? 4 : 2;
-    // the LDS-direct kernels also address a tile's rows with 32-bit byte offsets: 256 rows x stride < 2^31
+    // the LDS-direct kernels also address a tile's rows with 32-bit byte offsets: 256 rows x stride x 4 < 2^31
     return (g.N % 8) == 0 && qarvd_aligned16(g.Y) && ((g.ldy * esz) % 16) == 0 && qarvd_aligned16(g.s_n) &&
-           qarvd_aligned16(g.s_o) && qarvd_aligned16(g.bias) && g.ldxq <= (1 << 22) && g.ldwq <= (1 << 22);
+           qarvd_aligned16(g.s_o) && qarvd_aligned16(g.bias) && g.ldxq <= (1 << 22) && g.ldwq <= (1 << 22) && g.ldy <= (1 << 20);
 }
 
 bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)

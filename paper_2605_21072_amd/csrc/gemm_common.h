@@ -81,5 +81,7 @@ template <int BM, int BN, int WM, int WN, bool DUAL>
 qarvd_status launch_staged(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
 qarvd_status launch_dma(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
+qarvd_status launch_mfma16(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 
 }  // namespace qarvd_gemm

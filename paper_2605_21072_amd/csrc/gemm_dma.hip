@@ -39,7 +39,7 @@
 //     so that no stage wait of the next tile has output stores ahead of it in the memory counter.
 #include <algorithm>
 
-#include "gemm_common.h"
+#include "gemm_dma_common.h"
 
 #include <type_traits>
 
@@ -47,60 +47,11 @@ namespace qarvd_gemm {
 
 namespace {
 
-#ifndef QARVD_PROF
-#define QARVD_PROF 0
-#endif
-constexpr int BKD = 64;                   // K bytes per stage row
 // Output patch of a wave: 32 rows x 64 bytes (one 32x32 block of bf16, half a block of fp32), the
 // four 16-byte chunks of row r stored at chunk positions c ^ ((r >> 2) & 3) so that neither the
 // accumulator-layout writes nor the row-layout reads pile up on LDS banks.
 constexpr int PATCH_RS = 64;
 constexpr int PATCH_BYTES = 32 * PATCH_RS;
-
-#define QARVD_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
-#define QARVD_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
-
-typedef float v2f __attribute__((ext_vector_type(2)));
-// LDS is read and written through these native vector types only: accesses typed with the HIP
-// float4 / uint4 structs make the compiler drain every LDS-direct load in flight (s_waitcnt vmcnt(0))
-// before them, which would serialise the next tile's prefetch with the epilogue.
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef unsigned int v2u __attribute__((ext_vector_type(2)));
-typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-
-// Swizzle for 64-byte LDS rows (four 16-byte slots): any 8 consecutive rows spread over all
-// (row parity, slot) pairs and any 16 consecutive rows over all (row mod 4, slot) pairs.
-__device__ __forceinline__ int swz64(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | (((r >> 2) & 1) << 1); }
-
-// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14]).
-template <int N> __device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14)); }
-
-// One LDS-direct load: lane l moves the 16 bytes at base + voffset(l) + soffset to lds + 16*l (lds and
-// soffset wave-uniform).  The buffer descriptor (raw, no stride, no bounds) is rebuilt from `base` at
-// each call; it is wave-uniform, so the compiler keeps it in four SGPRs across the K loop.  The body
-// exists in the device pass only: the host pass has neither the descriptor type nor the builtin.
-__device__ __forceinline__ void buffer_load_lds16(const void *base, int voffset, int soffset, unsigned char *lds)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7fffffff, 0x00020000);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, QARVD_LPTR(lds), 16, voffset, soffset, 0, 0);
-#else
-    (void)base; (void)voffset; (void)soffset; (void)lds;
-#endif
-}
-
-// two fp32 -> packed bf16, round-to-nearest-even (one v_cvt_pk_bf16_f32)
-__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b)
-{
-    v2f f = {a, b};
-    v2bf h = __builtin_convertvector(f, v2bf);
-    return __builtin_bit_cast(uint32_t, h);
-}
 
 template <int BM, int BN, int WM, int WN, int NSTAGE>
 struct Geo {
@@ -393,15 +344,22 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     OutT *Y = reinterpret_cast<OutT *>(g.Y);
     constexpr int EPC = 16 / sizeof(OutT);          // output elements per 16-byte chunk
     const int pswz = (frow >> 2) & 3;               // chunk swizzle of this lane's patch row when writing
-    // patch -> global: 16 rows x 64 bytes per instruction, rows of the tile that exist only
-    auto flush_patch = [&](int i, int ncol0) {
+    // patch -> global: 16 rows x 64 bytes per instruction through a buffer descriptor over the rows of
+    // this tile that exist (rows below the matrix are dropped by its range check); the lane part of the
+    // address is one register per tile, the block part a scalar offset.
+    constexpr int ESZ = (int)sizeof(OutT);
+    unsigned char *const y_tile = reinterpret_cast<unsigned char *>(Y + (size_t)m0 * g.ldy);
+    const int ldy_b = (int)g.ldy * ESZ;
+    const int y_bytes = (min(BM, g.M - m0) - 1) * ldy_b + g.N * ESZ;
+    const int y_lane = (wm * G::WTM + (lane >> 2)) * ldy_b + (n0 + wn * G::WTN + (lane & 3) * EPC) * ESZ;
+    const int n_left = g.N - n0 - wn * G::WTN - (lane & 3) * EPC;     // columns from this lane's chunk to the matrix edge
+    auto flush_patch = [&](int i, int col0) {          // col0: first column of the pass inside the wave tile
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int row = p * 16 + (lane >> 2), ch = lane & 3;
             const v4i v = *reinterpret_cast<const v4i *>(patch + row * PATCH_RS + ((ch ^ ((row >> 2) & 3)) << 4));
-            const int m = m0 + wm * G::WTM + i * 32 + row;
-            const int n = ncol0 + ch * EPC;
-            if (m < g.M && n + EPC <= g.N) *reinterpret_cast<v4i *>(Y + (size_t)m * g.ldy + n) = v;
+            const int voff = col0 + EPC <= n_left ? y_lane : 0x7ffffff0;
+            buffer_store16(y_tile, y_bytes, voff, (i * 32 + p * 16) * ldy_b + col0 * ESZ, v);
         }
     };
     const bool has_o = DUAL && o_steps > 0;
@@ -485,11 +443,11 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
                     } else {
                         const int c = 2 * (q & 1) + fhalf;
                         *reinterpret_cast<v4f *>(patch + frow * PATCH_RS + ((c ^ pswz) << 4)) = v4f{y[0], y[1], y[2], y[3]};
-                        if (q & 1) flush_patch(i, n0 + wn * G::WTN + j * 32 + (q >> 1) * 16);
+                        if (q & 1) flush_patch(i, j * 32 + (q >> 1) * 16);
                     }
                 }
             }
-            if constexpr (sizeof(OutT) == 2) flush_patch(i, n0 + wn * G::WTN + j * 32);
+            if constexpr (sizeof(OutT) == 2) flush_patch(i, j * 32);
         }
     }
     };
@@ -530,19 +488,10 @@ qarvd_status launch_one(const GemmArgs &g, hipStream_t st)
     using G = Geo<BM, BN, WM, WN, NSTAGE>;
     auto k = gemm_dma_kernel<BM, BN, WM, WN, NSTAGE, DUAL, DBG, OutT>;
     QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
-    // persistent grid: as many workgroups as the chip holds at once, each walking the tile list with that stride
-    int dev = 0;
-    QARVD_HIP_TRY(hipGetDevice(&dev));
-    static int cu_count[64] = {0};              // per device, filled on first use (same value from any thread)
-    int cus = (dev >= 0 && dev < 64) ? cu_count[dev] : 0;
-    if (cus <= 0) {
-        QARVD_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        if (dev >= 0 && dev < 64) cu_count[dev] = cus;
-    }
     constexpr int LDS_PER_CU = 160 * 1024;
     const int wg_per_cu = std::max(1, std::min(LDS_PER_CU / G::LDS_BYTES, (G::WAVES_PER_EU * 4) / G::NW));
-    const int slots = std::max(8, cus * wg_per_cu / 8 * 8);      // a multiple of the XCD count keeps a workgroup's tiles on one XCD
-    const int grid = std::min(g.tiles_m * g.tiles_n, slots);
+    int grid = 0;
+    if (qarvd_status st_g = persistent_grid(g.tiles_m * g.tiles_n, wg_per_cu, &grid); st_g != QARVD_OK) return st_g;
     hipLaunchKernelGGL(k, dim3(grid), dim3(G::THREADS), G::LDS_BYTES, st, g);
     return qarvd_launch_status();
 }

@@ -197,7 +197,7 @@ def _pack(a, K, K_o):
 
 
 def _variants():
-    return list(range(0, 16))
+    return list(range(0, 20))
 
 
 @pytest.mark.parametrize("variant", _variants())
@@ -322,3 +322,37 @@ def test_full_size_layers_sampled_rows(name):
     o, mism = assert_layer_equal(L, torch.bfloat16, rows=np.unique(rows))
     assert mism == 0
     assert o["K_o"] == (spec.n_outlier + 31) // 32 * 32
+
+
+@pytest.mark.parametrize("layer", [wl.TARGET_LAYER, "cfg2.ffn_up.c0", "cfg2.ffn_down.c64"])
+def test_full_size_every_variant_sampled_rows(layer):
+    """Each kernel variant on full-size layers (several tiles per persistent workgroup, ragged last
+    row tile): raw accumulators and bf16 outputs of 40 sampled token rows against the oracle."""
+    spec = wl.find_layer(layer)
+    L = wl.make_layer(spec)
+    w = gpu_quantize_weight(L["W"])
+    Xq, sx = q.quant_act(dev(L["X"]), w.perm if w.K_o else None, w.K_o)
+    o = oracle.quantize_weight(L["W"])
+    rng = np.random.default_rng(spec.seed + 1)
+    rows = np.unique(np.concatenate([[0, spec.M - 1], rng.choice(spec.M, 38, replace=False)]))
+    Xq_o, sx_o = oracle.quant_act(L["X"][rows], o["perm"])
+    ref = oracle.dual_gemm(Xq_o, sx_o, o["Wq"], o["s_normal"], o["s_outlier"], L["bias"], o["K_o"])
+    rt = torch.from_numpy(rows).cuda()
+    ran = 0
+    for variant in range(1, q.gemm_num_variants() + 1):
+        try:
+            Y, an, ao = q.w8a8_dual_gemm(Xq, sx, w, dev(L["bias"]), spec.M, torch.bfloat16, debug_acc=True, variant=variant)
+        except q.QarvdError as e:
+            if e.status == -2:                       # this variant cannot run the shape
+                continue
+            raise
+        torch.cuda.synchronize()
+        assert np.array_equal(an[rt].cpu().numpy(), ref["acc_n"]), q.gemm_variant_name(variant)
+        assert np.array_equal(ao[rt].cpu().numpy(), ref["acc_o"]), q.gemm_variant_name(variant)
+        assert check_y(Y[rt], ref) == 0, q.gemm_variant_name(variant)
+        # the timed path (no accumulator dumps) must give the same bytes
+        Y2 = q.w8a8_dual_gemm(Xq, sx, w, dev(L["bias"]), spec.M, torch.bfloat16, variant=variant)
+        torch.cuda.synchronize()
+        assert torch.equal(Y2.view(torch.int16), Y.view(torch.int16)), q.gemm_variant_name(variant)
+        ran += 1
+    assert ran >= 4
