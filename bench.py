@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16", action="store_true")
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant (0 = heuristic)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a 256 MiB device-to-device copy (reference dispatch for scaling the HBM traffic counters)")
     return ap.parse_args()
 
 
@@ -58,6 +60,14 @@ def main():
     q.load_library()
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        a = torch.full((256 << 20,), 3, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": int(a.numel())}))
+        return
 
     specs = wl.config_layers(args.config)
     if args.layers:

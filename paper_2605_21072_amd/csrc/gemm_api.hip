@@ -19,6 +19,10 @@ const Variant kVariants[] = {
     {"lds-direct 128x128 (4 waves, 4 stages) single", 128, 128, 0, true, launch_dma<128, 128, 2, 2, 4, false>},
     {"lds-direct 256x256 (8 waves, 4 stages) dual", 256, 256, 128, true, launch_dma<256, 256, 2, 4, 4, true>},
     {"lds-direct 256x256 (8 waves, 4 stages) single", 256, 256, 0, true, launch_dma<256, 256, 2, 4, 4, false>},
+    {"lds-direct 256x128 (8 waves, 4 stages) dual", 256, 128, 128, true, launch_dma<256, 128, 4, 2, 4, true>},
+    {"lds-direct 256x128 (8 waves, 4 stages) single", 256, 128, 0, true, launch_dma<256, 128, 4, 2, 4, false>},
+    {"lds-direct 128x256 (8 waves, 4 stages) dual", 128, 256, 128, true, launch_dma<128, 256, 2, 4, 4, true>},
+    {"lds-direct 128x256 (8 waves, 4 stages) single", 128, 256, 0, true, launch_dma<128, 256, 2, 4, 4, false>},
     {"16x16x64 256x224 (8 waves, 4 stages) dual", 256, 224, 128, true, launch_mfma16<256, 224, 4, 2, 4, true>},
     {"16x16x64 256x224 (8 waves, 4 stages) single", 256, 224, 0, true, launch_mfma16<256, 224, 4, 2, 4, false>},
 };
@@ -39,26 +43,31 @@ bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)
     return true;
 }
 
-// Heuristic.  Measured on MI355X the MFMA loop of every LDS-direct variant runs at about the same
-// chip-wide rate (the INT8 MFMA clock is power-limited), so what separates them is how many
-// "rounds" of tiles the busiest CU sees: cost = rounds x tile area x workgroups sharing a CU.
-// Ties go to the larger tile (half the L1/L2 operand traffic per MAC); the three-stage four-wave
-// tiles carry a penalty because only one stage can be in flight behind the one being read.
+// Heuristic: a three-constant cost model per LDS-direct variant, fitted to timings on MI355X over the
+// DiT shapes (M = 520..4680, N and K in {1536, 5120, 8960, 13824}):
+//     time ~ c + ceil(tiles / 256) * (a + b * T),     T = packed K / 64
+// c is launch plus the first tile's lead-in, a a tile's epilogue and hand-over, b one K iteration of a
+// tile that has its CU to itself (two four-wave workgroups sharing a CU each run at half speed, which
+// the ceil over 256 CUs already accounts for).  The 256x256 tile has the cheapest iteration per MAC and
+// wins when N is wide; the 128x256 eight-wave tile fills the chip when N = 1536; the 128x128 tile wins
+// for short M; the 16x16x64 kernel overtakes the 256x256 one once K is long enough to amortise its
+// dearer epilogue, because the chip holds a higher clock under its MFMA mix.
 int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
 {
     const bool dual = g.n_off > 0;
     if (g.n_off <= 128 && vector_out_ok(g, ydt)) {
-        struct Cand { int variant, bm, bn, wg_per_cu; double penalty; };
-        const Cand cand[4] = {{dual ? 11 : 12, 256, 256, 1, 1.00},
-                              {dual ? 9 : 10, 128, 128, 2, 1.02},
-                              {dual ? 5 : 6, 256, 128, 2, 1.12},
-                              {dual ? 7 : 8, 192, 128, 2, 1.12}};
+        struct Cand { int variant, bm, bn; double c, a, b; };
+        const Cand cand[5] = {{dual ? 11 : 12, 256, 256, 2.2, 8.9, 0.688},
+                              {dual ? 17 : 18, 256, 224, 4.0, 11.5, 0.621},
+                              {dual ? 15 : 16, 128, 256, 5.0, 2.75, 0.490},
+                              {dual ? 13 : 14, 256, 128, 5.0, 3.0, 0.508},
+                              {dual ? 9 : 10, 128, 128, 2.0, 1.5, 0.309}};
+        const double T = g.kp / 64;
         int best = cand[0].variant;
         double best_cost = 1e300;
         for (const Cand &c : cand) {
             const long tiles = (long)((g.M + c.bm - 1) / c.bm) * ((g.N + c.bn - 1) / c.bn);
-            const long rounds = (tiles + 256L * c.wg_per_cu - 1) / (256L * c.wg_per_cu);
-            const double cost = (double)rounds * c.wg_per_cu * c.bm * c.bn * c.penalty;
+            const double cost = c.c + (double)((tiles + 255) / 256) * (c.a + c.b * T);
             if (cost < best_cost) {
                 best_cost = cost;
                 best = c.variant;

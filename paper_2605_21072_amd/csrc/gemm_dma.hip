@@ -70,7 +70,7 @@ struct Geo {
     static constexpr int LDS_BYTES = SCALES_OFF + 2 * NSCALE * (int)sizeof(float);   // two scale buffers: tile t uses buffer t & 1
     static constexpr int SPT = (NSCALE + THREADS - 1) / THREADS;   // scale values per thread
     static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "row groups must divide over the waves");
-    static_assert(WTM % 32 == 0 && WTN % 64 == 0, "wave tile is TM x TN blocks, TN even (a patch pass holds 64 bf16 columns)");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is TM x TN blocks of 32 x 32");
     // accumulators beyond 128 registers per lane need the whole register file: one wave per SIMD
     static constexpr int WAVES_PER_EU = (TM * TN * 16 > 128) ? 1 : 2;
     static_assert(NSTAGE >= 3, "two head tiles plus one free stage");
@@ -516,6 +516,8 @@ qarvd_status launch_dma(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     template qarvd_status launch_dma<BM, BN, WM, WN, NS, true>(const GemmArgs &, qarvd_dtype, hipStream_t); \
     template qarvd_status launch_dma<BM, BN, WM, WN, NS, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
 QARVD_INST(256, 256, 2, 4, 4)
+QARVD_INST(256, 128, 4, 2, 4)
+QARVD_INST(128, 256, 2, 4, 4)
 QARVD_INST(256, 128, 2, 2, 3)
 QARVD_INST(192, 128, 2, 2, 3)
 QARVD_INST(128, 128, 2, 2, 4)
