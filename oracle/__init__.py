@@ -118,8 +118,9 @@ def quantize_rows(W, perm, K_o):
     return Wq, sn, so
 
 
-def quantize_weight(W, tau=3.5, alpha=1.2, align=32, forced_mask=None):
-    """Returns dict(Wq, s_normal, s_outlier, perm, K_o, v, flag, stats)."""
+def quantize_weight(W, tau=3.5, alpha=1.2, align=32, forced_mask=None, bits=8):
+    """Returns dict(Wq, s_normal, s_outlier, perm, K_o, v, flag, stats).  bits=4: codes in [-7, 7]
+    (one per int8 element), scales = block absmax / 7 (the W4A8 setting of Sec. 4.2)."""
     W = _f32(W)
     N, K = W.shape
     Wq = np.empty((N, K), np.int8)
@@ -131,8 +132,8 @@ def quantize_weight(W, tau=3.5, alpha=1.2, align=32, forced_mask=None):
     st = np.zeros(4, np.float64)
     ko = C.c_int32(0)
     fm = None if forced_mask is None else np.ascontiguousarray(forced_mask, dtype=np.uint8)
-    _check(_load().oracle_quantize_weight(
-        _p(W, C.c_float), N, K, C.c_double(tau), C.c_double(alpha), int(align), _p(fm, C.c_uint8),
+    _check(_load().oracle_quantize_weight_bits(
+        _p(W, C.c_float), N, K, C.c_double(tau), C.c_double(alpha), int(align), _p(fm, C.c_uint8), int(bits),
         _p(Wq, C.c_int8), _p(sn, C.c_float), _p(so, C.c_float), _p(perm, C.c_int32), C.byref(ko),
         _p(v, C.c_float), _p(flag, C.c_uint8), _p(st, C.c_double)))
     return dict(Wq=Wq, s_normal=sn, s_outlier=so, perm=perm, K_o=int(ko.value), v=v, flag=flag,

@@ -72,19 +72,24 @@ static double median_of(const double *x, int n)
     return m;
 }
 
-/* Eq. (quantization) with z = 0, q in [-127, 127]; s == 0 -> 0. */
-static int8_t quantize_one(float x, float s)
+/*
+ * Eq. (quantization) with z = 0 and the symmetric range q in [-qmax, qmax],
+ * qmax = 2^(b-1) - 1 (127 for b = 8, 7 for b = 4); s == 0 -> 0.
+ */
+static int8_t quantize_sym(float x, float s, float qmax)
 {
     float r;
     if (s == 0.0f)
         return 0;
     r = rintf(x / s); /* round-half-to-even in the default rounding mode */
-    if (r > 127.0f)
-        r = 127.0f;
-    if (r < -127.0f)
-        r = -127.0f;
+    if (r > qmax)
+        r = qmax;
+    if (r < -qmax)
+        r = -qmax;
     return (int8_t)r;
 }
+
+static int8_t quantize_one(float x, float s) { return quantize_sym(x, s, 127.0f); }
 
 /* float -> bfloat16 bits, round-to-nearest-even (finite inputs). */
 static uint16_t bf16_rne(float f)
@@ -215,11 +220,18 @@ int oracle_build_perm(const uint8_t *sel, int K, int32_t *perm, int *K_o)
  * Dual-scale weight quantization for a given split (Eq. (dual_scale), Eq.
  * (quantization), one scale per output row per block).
  */
-int oracle_quantize_rows(const float *W, int N, int K, const int32_t *perm, int K_o,
-                         int8_t *Wq, float *s_normal, float *s_outlier)
+/*
+ * `bits` = 8 or 4: the weight bit-width of the W8A8 and W4A8 settings (Sec. 4.2).  The codes are
+ * returned one per int8 either way; only their range and the scale divisor (2^(bits-1) - 1) differ.
+ */
+int oracle_quantize_rows_bits(const float *W, int N, int K, const int32_t *perm, int K_o, int bits,
+                              int8_t *Wq, float *s_normal, float *s_outlier)
 {
-    if (!W || !perm || !Wq || !s_normal || !s_outlier || N <= 0 || K <= 0 || K_o < 0 || K_o > K)
+    float qmax;
+    if (!W || !perm || !Wq || !s_normal || !s_outlier || N <= 0 || K <= 0 || K_o < 0 || K_o > K ||
+        (bits != 8 && bits != 4))
         return ORACLE_BAD_ARG;
+    qmax = bits == 8 ? 127.0f : 7.0f;
 #pragma omp parallel for schedule(static)
     for (int j = 0; j < N; ++j) {
         const float *w = W + (size_t)j * K;
@@ -234,16 +246,22 @@ int oracle_quantize_rows(const float *W, int N, int K, const int32_t *perm, int 
             if (a > a_n)
                 a_n = a;
         }
-        so = a_o / 127.0f;
-        sn = a_n / 127.0f;
+        so = a_o / qmax;
+        sn = a_n / qmax;
         s_outlier[j] = so;
         s_normal[j] = sn;
         for (int p = 0; p < K_o; ++p)
-            Wq[(size_t)j * K + p] = quantize_one(w[perm[p]], so);
+            Wq[(size_t)j * K + p] = quantize_sym(w[perm[p]], so, qmax);
         for (int p = K_o; p < K; ++p)
-            Wq[(size_t)j * K + p] = quantize_one(w[perm[p]], sn);
+            Wq[(size_t)j * K + p] = quantize_sym(w[perm[p]], sn, qmax);
     }
     return ORACLE_OK;
+}
+
+int oracle_quantize_rows(const float *W, int N, int K, const int32_t *perm, int K_o,
+                         int8_t *Wq, float *s_normal, float *s_outlier)
+{
+    return oracle_quantize_rows_bits(W, N, K, perm, K_o, 8, Wq, s_normal, s_outlier);
 }
 
 /*
@@ -252,10 +270,10 @@ int oracle_quantize_rows(const float *W, int N, int K, const int32_t *perm, int 
  * detection and alignment.  Optional outputs (nullable): v_out[K], flag_out[K]
  * (raw detector flags before alignment), stats[4].
  */
-int oracle_quantize_weight(const float *W, int N, int K, double tau, double alpha, int align,
-                           const uint8_t *forced_mask, int8_t *Wq, float *s_normal,
-                           float *s_outlier, int32_t *perm, int32_t *K_o_out, float *v_out,
-                           uint8_t *flag_out, double *stats)
+int oracle_quantize_weight_bits(const float *W, int N, int K, double tau, double alpha, int align,
+                                const uint8_t *forced_mask, int bits, int8_t *Wq, float *s_normal,
+                                float *s_outlier, int32_t *perm, int32_t *K_o_out, float *v_out,
+                                uint8_t *flag_out, double *stats)
 {
     float *v;
     uint8_t *sel;
@@ -282,7 +300,7 @@ int oracle_quantize_weight(const float *W, int N, int K, double tau, double alph
     if (rc == ORACLE_OK)
         rc = oracle_build_perm(sel, K, perm, &K_o);
     if (rc == ORACLE_OK)
-        rc = oracle_quantize_rows(W, N, K, perm, K_o, Wq, s_normal, s_outlier);
+        rc = oracle_quantize_rows_bits(W, N, K, perm, K_o, bits, Wq, s_normal, s_outlier);
     if (rc == ORACLE_OK) {
         *K_o_out = K_o;
         if (v_out)
@@ -291,6 +309,15 @@ int oracle_quantize_weight(const float *W, int N, int K, double tau, double alph
     free(v);
     free(sel);
     return rc;
+}
+
+int oracle_quantize_weight(const float *W, int N, int K, double tau, double alpha, int align,
+                           const uint8_t *forced_mask, int8_t *Wq, float *s_normal,
+                           float *s_outlier, int32_t *perm, int32_t *K_o_out, float *v_out,
+                           uint8_t *flag_out, double *stats)
+{
+    return oracle_quantize_weight_bits(W, N, K, tau, alpha, align, forced_mask, 8, Wq, s_normal,
+                                       s_outlier, perm, K_o_out, v_out, flag_out, stats);
 }
 
 /* --------------------------------- activation quantization (App., kernel i) */
