@@ -157,6 +157,44 @@ qarvd_status qarvd_w8a8_dual_gemm(const int8_t *Xq, int64_t ldxq, const float *s
                                   int32_t *dbg_acc_normal, int32_t *dbg_acc_outlier, void *stream);
 
 /*
+ * W4A8 (Sec. 4.2, the W4A8 rows of the result tables; Sec. 4.3: the dual scale matters most at low
+ * weight bit-width).  Same steps as qarvd_quantize_weight with Eq. (quantization) at b = 4:
+ *     s = max|W[j, block]| / 7,  code = clip(rint(W / s), -7, 7)
+ * and the codes stored two per byte.  Packed INT4 row: the packed K axis of the INT8 layout, each
+ * aligned group of 16 positions 16g..16g+15 in 8 bytes at byte offset 8g: byte i (i < 4) holds
+ * position 16g+i in its low nibble and 16g+4+i in its high nibble, byte 4+i positions 16g+8+i and
+ * 16g+12+i (two's-complement nibbles).  Row extent qarvd_packed_k(K, K_o) / 2 bytes.
+ *   Wq4   out  u8 [N, ldwq4]; ldwq4 in BYTES, >= qarvd_packed_k(K, -1) / 2, multiple of 16
+ *   workspace  >= qarvd_quantize_weight_w4_workspace(N, K) bytes (it also holds one byte per code
+ *              of the whole matrix until they are packed), 256-byte aligned
+ * Everything else as qarvd_quantize_weight.  Synchronises `stream`.
+ */
+size_t qarvd_quantize_weight_w4_workspace(int32_t N, int32_t K);
+qarvd_status qarvd_quantize_weight_w4(const float *W, int32_t N, int32_t K, int64_t ldw,
+                                      const qarvd_detect_cfg *cfg, uint8_t *Wq4, int64_t ldwq4,
+                                      float *s_normal, float *s_outlier, int32_t *perm,
+                                      int32_t *K_o_host, float *v_out, void *workspace,
+                                      size_t workspace_bytes, void *stream);
+
+/*
+ * ONLINE GEMM + de-quantization on packed INT4 weights: the operation of qarvd_w8a8_dual_gemm with
+ * Wq given in the layout above.  The nibbles are widened to INT8 in registers (each code times 16,
+ * which the scales undo exactly), so both INT32 sums and every output are those of the INT8 path on
+ * the same codes.
+ *   Wq4  in  packed u8 [N, ldwq4] for the same (K, K_o) as Xq; 16-byte aligned, ldwq4 % 16 == 0
+ * Needs the fast-path preconditions (N % 8 == 0, 16-byte aligned Y rows, scales and bias, outlier
+ * block of at most 128 packed bytes); otherwise returns QARVD_ERR_UNSUPPORTED.  variant: 0 = heuristic,
+ * 1..qarvd_w4_gemm_num_variants() pick a kernel.  Fully asynchronous on `stream`.
+ */
+qarvd_status qarvd_w4a8_dual_gemm(const int8_t *Xq, int64_t ldxq, const float *s_x,
+                                  const uint8_t *Wq4, int64_t ldwq4, const float *s_normal,
+                                  const float *s_outlier, const float *bias, int32_t M, int32_t N,
+                                  int32_t K, int32_t K_o, void *Y, qarvd_dtype ydt, int64_t ldy,
+                                  int32_t *dbg_acc_normal, int32_t *dbg_acc_outlier, int32_t variant,
+                                  void *stream);
+int32_t qarvd_w4_gemm_num_variants(void);
+
+/*
  * Same operation with the kernel variant chosen by the caller instead of the built-in
  * heuristic (variant 0 = heuristic).  qarvd_gemm_num_variants() is the count of selectable
  * variants (1..count); qarvd_gemm_variant_name(i) describes one.  A variant that cannot run

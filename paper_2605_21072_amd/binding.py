@@ -69,6 +69,14 @@ def load_library():
     lib.qarvd_w8a8_dual_gemm.restype = C.c_int
     lib.qarvd_w8a8_dual_gemm_variant.argtypes = [i32] + gemm_args
     lib.qarvd_w8a8_dual_gemm_variant.restype = C.c_int
+    lib.qarvd_quantize_weight_w4_workspace.argtypes = [i32, i32]
+    lib.qarvd_quantize_weight_w4_workspace.restype = C.c_size_t
+    lib.qarvd_quantize_weight_w4.argtypes = lib.qarvd_quantize_weight.argtypes
+    lib.qarvd_quantize_weight_w4.restype = C.c_int
+    lib.qarvd_w4a8_dual_gemm.argtypes = gemm_args[:-1] + [i32, C.c_void_p]
+    lib.qarvd_w4a8_dual_gemm.restype = C.c_int
+    lib.qarvd_w4_gemm_num_variants.argtypes = []
+    lib.qarvd_w4_gemm_num_variants.restype = i32
     lib.qarvd_gemm_num_variants.argtypes = []
     lib.qarvd_gemm_num_variants.restype = i32
     lib.qarvd_gemm_variant_name.argtypes = [i32]
@@ -147,6 +155,7 @@ class DualScaleWeight:
     N: int
     K: int
     v: Optional[torch.Tensor] = None   # f32 [K] column norms
+    bits: int = 8                      # 4: Wq is uint8 [N, ldwq4], two INT4 codes per byte (see qarvd.h)
 
     @property
     def kp(self) -> int:
@@ -156,29 +165,45 @@ class DualScaleWeight:
     def n_off(self) -> int:
         return packed_normal_offset(self.K_o)
 
+    def codes(self) -> torch.Tensor:
+        """int8 [N, kp]: one code per packed position (the INT4 layout unpacked; marshalling only)."""
+        if self.bits == 8:
+            return self.Wq[:, :self.kp]
+        b = self.Wq[:, :self.kp // 2].to(torch.int16).reshape(self.N, -1, 8)       # groups of 16 positions
+        lo = ((b & 0xF) ^ 8) - 8
+        hi = (((b >> 4) & 0xF) ^ 8) - 8
+        g = torch.stack([lo[:, :, 0:4], hi[:, :, 0:4], lo[:, :, 4:8], hi[:, :, 4:8]], dim=2)   # [N, G, 4, 4]
+        return g.reshape(self.N, -1).to(torch.int8)
+
     def logical_Wq(self) -> torch.Tensor:
         """int8 [N, K] in packed channel order without the zero padding."""
-        return torch.cat([self.Wq[:, :self.K_o], self.Wq[:, self.n_off:self.n_off + self.K - self.K_o]], dim=1)
+        c = self.codes()
+        return torch.cat([c[:, :self.K_o], c[:, self.n_off:self.n_off + self.K - self.K_o]], dim=1)
 
 
 def quantize_weight(W: torch.Tensor, tau: float = 3.5, alpha: float = 1.2, align: int = 32,
                     forced_mask=None, ldwq: Optional[int] = None, want_norms: bool = True,
-                    stream=None) -> DualScaleWeight:
-    """qarvd_quantize_weight: W f32 [N,K] on the device -> packed dual-scale layer."""
+                    stream=None, bits: int = 8) -> DualScaleWeight:
+    """qarvd_quantize_weight (bits=8) / qarvd_quantize_weight_w4 (bits=4): W f32 [N,K] on the device ->
+    packed dual-scale layer.  For bits=4 `ldwq` is in bytes (two codes per byte)."""
     lib = load_library()
     _dev2d(W, "W")
     if W.dtype != torch.float32:
         raise TypeError("W must be float32")
     N, K = W.shape
     dev = W.device
+    if bits not in (4, 8):
+        raise ValueError("bits must be 4 or 8")
     if ldwq is None:
         ldwq = packed_k(K, -1) if (forced_mask is not None or align % 32) else (K + 127) // 128 * 128
-    Wq = torch.empty((N, ldwq), dtype=torch.int8, device=dev)
+        if bits == 4:
+            ldwq //= 2
+    Wq = torch.empty((N, ldwq), dtype=torch.int8 if bits == 8 else torch.uint8, device=dev)
     sn = torch.empty(N, dtype=torch.float32, device=dev)
     so = torch.empty(N, dtype=torch.float32, device=dev)
     perm = torch.empty(K, dtype=torch.int32, device=dev)
     v = torch.empty(K, dtype=torch.float32, device=dev) if want_norms else None
-    ws_bytes = quantize_weight_workspace(N, K)
+    ws_bytes = quantize_weight_workspace(N, K) if bits == 8 else int(lib.qarvd_quantize_weight_w4_workspace(N, K))
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
     ws_ptr = (ws.data_ptr() + 255) // 256 * 256
     cfg = _DetectCfg(float(tau), float(alpha), int(align), None)
@@ -190,11 +215,12 @@ def quantize_weight(W: torch.Tensor, tau: float = 3.5, alpha: float = 1.2, align
             raise ValueError("forced_mask must have K entries")
         cfg.forced_mask = keep.ctypes.data
     ko = C.c_int32(-1)
-    st = lib.qarvd_quantize_weight(_ptr(W), N, K, W.stride(0), C.byref(cfg), _ptr(Wq), ldwq, _ptr(sn), _ptr(so),
-                                   _ptr(perm), C.byref(ko), _ptr(v), C.c_void_p(ws_ptr), ws_bytes, _stream(stream))
-    _check(st, "qarvd_quantize_weight")
+    fn = lib.qarvd_quantize_weight if bits == 8 else lib.qarvd_quantize_weight_w4
+    st = fn(_ptr(W), N, K, W.stride(0), C.byref(cfg), _ptr(Wq), ldwq, _ptr(sn), _ptr(so),
+            _ptr(perm), C.byref(ko), _ptr(v), C.c_void_p(ws_ptr), ws_bytes, _stream(stream))
+    _check(st, "qarvd_quantize_weight" if bits == 8 else "qarvd_quantize_weight_w4")
     del keep
-    return DualScaleWeight(Wq, sn, so, perm, int(ko.value), N, K, v)
+    return DualScaleWeight(Wq, sn, so, perm, int(ko.value), N, K, v, bits)
 
 
 def quant_act(X: torch.Tensor, perm: Optional[torch.Tensor], K_o: int, Xq: Optional[torch.Tensor] = None,
@@ -230,7 +256,8 @@ def quant_act_static(X: torch.Tensor, perm: Optional[torch.Tensor], K_o: int, sc
 def w8a8_dual_gemm(Xq: torch.Tensor, s_x: torch.Tensor, w: DualScaleWeight, bias: Optional[torch.Tensor], M: int,
                    out_dtype=torch.bfloat16, Y: Optional[torch.Tensor] = None, debug_acc: bool = False,
                    variant: int = 0, stream=None):
-    """qarvd_w8a8_dual_gemm.  Returns Y, or (Y, acc_normal, acc_outlier) with debug_acc."""
+    """qarvd_w8a8_dual_gemm (or qarvd_w4a8_dual_gemm when `w` holds INT4 codes).  Returns Y, or
+    (Y, acc_normal, acc_outlier) with debug_acc."""
     lib = load_library()
     if Y is None:
         Y = torch.empty((M, w.N), dtype=out_dtype, device=Xq.device)
@@ -238,6 +265,12 @@ def w8a8_dual_gemm(Xq: torch.Tensor, s_x: torch.Tensor, w: DualScaleWeight, bias
     if debug_acc:
         an = torch.empty((M, w.N), dtype=torch.int32, device=Xq.device)
         ao = torch.empty((M, w.N), dtype=torch.int32, device=Xq.device)
+    if w.bits == 4:
+        st = lib.qarvd_w4a8_dual_gemm(_ptr(Xq), Xq.stride(0), _ptr(s_x), _ptr(w.Wq), w.Wq.stride(0),
+                                      _ptr(w.s_normal), _ptr(w.s_outlier), _ptr(bias), M, w.N, w.K, w.K_o,
+                                      _ptr(Y), _dt(Y), Y.stride(0), _ptr(an), _ptr(ao), variant, _stream(stream))
+        _check(st, "qarvd_w4a8_dual_gemm")
+        return (Y, an, ao) if debug_acc else Y
     st = lib.qarvd_w8a8_dual_gemm_variant(variant, _ptr(Xq), Xq.stride(0), _ptr(s_x), _ptr(w.Wq), w.Wq.stride(0),
                                           _ptr(w.s_normal), _ptr(w.s_outlier), _ptr(bias), M, w.N, w.K, w.K_o,
                                           _ptr(Y), _dt(Y), Y.stride(0), _ptr(an), _ptr(ao), _stream(stream))

@@ -131,3 +131,56 @@ extern "C" qarvd_status qarvd_w8a8_dual_gemm(const int8_t *Xq, int64_t ldxq, con
     return qarvd_w8a8_dual_gemm_variant(0, Xq, ldxq, s_x, Wq, ldwq, s_normal, s_outlier, bias, M, N, K, K_o, Y, ydt,
                                         ldy, dbg_acc_normal, dbg_acc_outlier, stream);
 }
+
+// ---- W4A8: packed INT4 weights, the same kernels with the W operand widened in registers ----
+namespace {
+using namespace qarvd_gemm;
+struct W4Variant {
+    int BM, BN;
+    qarvd_status (*dual)(const GemmArgs &, qarvd_dtype, hipStream_t);
+    qarvd_status (*single)(const GemmArgs &, qarvd_dtype, hipStream_t);
+};
+const W4Variant kW4Variants[] = {
+    {256, 256, launch_dma<256, 256, 2, 4, 4, true, true>, launch_dma<256, 256, 2, 4, 4, false, true>},
+    {128, 128, launch_dma<128, 128, 2, 2, 4, true, true>, launch_dma<128, 128, 2, 2, 4, false, true>},
+};
+constexpr int kNumW4Variants = sizeof(kW4Variants) / sizeof(kW4Variants[0]);
+}  // namespace
+
+extern "C" int32_t qarvd_w4_gemm_num_variants(void) { return kNumW4Variants; }
+
+extern "C" qarvd_status qarvd_w4a8_dual_gemm(const int8_t *Xq, int64_t ldxq, const float *s_x, const uint8_t *Wq4,
+                                             int64_t ldwq4, const float *s_normal, const float *s_outlier,
+                                             const float *bias, int32_t M, int32_t N, int32_t K, int32_t K_o, void *Y,
+                                             qarvd_dtype ydt, int64_t ldy, int32_t *dbg_acc_normal,
+                                             int32_t *dbg_acc_outlier, int32_t variant, void *stream)
+{
+    if (!Xq || !Wq4 || !s_x || !s_normal || !s_outlier || !Y) return QARVD_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0 || K <= 0 || K > QARVD_MAX_K || K_o < 0 || K_o > K) return QARVD_ERR_INVALID_ARG;
+    if (variant < 0 || variant > kNumW4Variants) return QARVD_ERR_INVALID_ARG;
+    const PackedK pk = qarvd_packed(K, K_o);
+    if (ldxq < pk.kp || ldwq4 < pk.kp / 2 || ldy < N) return QARVD_ERR_INVALID_ARG;
+    if (ydt != QARVD_F32 && ydt != QARVD_BF16) return QARVD_ERR_UNSUPPORTED;
+    if (!qarvd_aligned16(Xq) || !qarvd_aligned16(Wq4) || (ldxq % 16) || (ldwq4 % 16)) return QARVD_ERR_UNSUPPORTED;
+    const size_t esz = ydt == QARVD_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(Y) % esz) return QARVD_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(s_x) | reinterpret_cast<uintptr_t>(s_normal) | reinterpret_cast<uintptr_t>(s_outlier) |
+         reinterpret_cast<uintptr_t>(bias) | reinterpret_cast<uintptr_t>(dbg_acc_normal) |
+         reinterpret_cast<uintptr_t>(dbg_acc_outlier)) & 3u)
+        return QARVD_ERR_UNSUPPORTED;
+    GemmArgs g;
+    g.Xq = Xq; g.Wq = reinterpret_cast<const int8_t *>(Wq4); g.s_x = s_x; g.s_n = s_normal; g.s_o = s_outlier; g.bias = bias;
+    g.Y = Y; g.dbg_n = dbg_acc_normal; g.dbg_o = dbg_acc_outlier;
+    g.ldxq = ldxq; g.ldwq = ldwq4; g.ldy = ldy; g.M = M; g.N = N; g.n_off = pk.n_off; g.kp = pk.kp;
+    g.tiles_m = g.tiles_n = 0;
+    if (g.n_off > 128 || !vector_out_ok(g, ydt)) return QARVD_ERR_UNSUPPORTED;
+    if (variant == 0) {     // same cost model as the INT8 path, restricted to the two tiles built for INT4
+        const double T = g.kp / 64;
+        const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256), t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+        const double c256 = 2.2 + (double)((t256 + 255) / 256) * (8.9 + 0.688 * T);
+        const double c128 = 2.0 + (double)((t128 + 255) / 256) * (1.5 + 0.309 * T);
+        variant = c256 <= c128 ? 1 : 2;
+    }
+    const W4Variant &v = kW4Variants[variant - 1];
+    return (g.n_off > 0 ? v.dual : v.single)(g, ydt, reinterpret_cast<hipStream_t>(stream));
+}

@@ -19,6 +19,7 @@
 
 namespace qarvd_gemm {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
@@ -79,7 +80,7 @@ struct Variant {
 // launchers defined in gemm_staged.hip / gemm_dma.hip
 template <int BM, int BN, int WM, int WN, bool DUAL>
 qarvd_status launch_staged(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool W4 = false>   // W4: Wq is packed INT4, ldwq in bytes
 qarvd_status launch_dma(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
 qarvd_status launch_mfma16(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);

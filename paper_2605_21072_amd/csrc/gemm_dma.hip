@@ -53,15 +53,18 @@ namespace {
 constexpr int PATCH_RS = 64;
 constexpr int PATCH_BYTES = 32 * PATCH_RS;
 
-template <int BM, int BN, int WM, int WN, int NSTAGE>
+// W4: the W operand is packed INT4 (32 bytes per row and stage instead of 64).
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool W4 = false>
 struct Geo {
     static constexpr int NW = WM * WN;                 // wavefronts
     static constexpr int THREADS = 64 * NW;
     static constexpr int WTM = BM / WM, WTN = BN / WN; // wave tile
     static constexpr int TM = WTM / 32, TN = WTN / 32; // 32x32 blocks per wave
-    static constexpr int NA = BM / 16 / NW, NB = BN / 16 / NW;   // LDS-direct loads per wave per stage
+    static constexpr int WROW = W4 ? 32 : BKD;          // bytes of a W row in a stage
+    static constexpr int WGRP = W4 ? 32 : 16;           // W rows one LDS-direct load covers (1 KB)
+    static constexpr int NA = BM / 16 / NW, NB = BN / WGRP / NW;   // LDS-direct loads per wave per stage
     static constexpr int NLOAD = NA + NB;
-    static constexpr int STG = (BM + BN) * BKD;
+    static constexpr int STG = BM * BKD + BN * WROW;
     static constexpr int PATCHES = NW * PATCH_BYTES;   // all of them fit into the one stage read last before the head tiles
     // where the output patches go: inside one free stage, split over two free stages, or behind the stages
     static_assert(PATCHES <= STG, "the output patches share one free stage");
@@ -69,17 +72,25 @@ struct Geo {
     static constexpr int NSCALE = BM + 3 * BN;
     static constexpr int LDS_BYTES = SCALES_OFF + 2 * NSCALE * (int)sizeof(float);   // two scale buffers: tile t uses buffer t & 1
     static constexpr int SPT = (NSCALE + THREADS - 1) / THREADS;   // scale values per thread
-    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "row groups must divide over the waves");
+    static_assert(BM % (16 * NW) == 0 && BN % (WGRP * NW) == 0, "row groups must divide over the waves");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is TM x TN blocks of 32 x 32");
     // accumulators beyond 128 registers per lane need the whole register file: one wave per SIMD
     static constexpr int WAVES_PER_EU = (TM * TN * 16 > 128) ? 1 : 2;
     static_assert(NSTAGE >= 3, "two head tiles plus one free stage");
 };
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool DBG, typename OutT>
-__global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_PER_EU)) void gemm_dma_kernel(GemmArgs g)
+// widen eight packed INT4 codes (two dwords) to sixteen INT8 lanes, each code times 16: with the nibble
+// order of the packed layout, (p << 4) & 0xF0F0F0F0 are four consecutive codes and p & 0xF0F0F0F0 the next four
+__device__ __forceinline__ v4i unpack_w4(v2i p)
 {
-    using G = Geo<BM, BN, WM, WN, NSTAGE>;
+    const int m = (int)0xF0F0F0F0u;
+    return v4i{(p.x << 4) & m, p.x & m, (p.y << 4) & m, p.y & m};
+}
+
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool DBG, typename OutT, bool W4>
+__global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAVES_PER_EU)) void gemm_dma_kernel(GemmArgs g)
+{
+    using G = Geo<BM, BN, WM, WN, NSTAGE, W4>;
     constexpr int TM = G::TM, TN = G::TN, NA = G::NA, NB = G::NB, NW = G::NW, STG = G::STG;
     constexpr int AHEAD = NSTAGE - 1;                  // stages in flight
     extern __shared__ __align__(16) unsigned char smem[];
@@ -117,8 +128,14 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
         for (int i = 0; i < NA; ++i)
             va[i] = (min(lm0 + (NW * i + wave) * 16 + drow, g.M - 1) - lm0) * (int)g.ldxq + dchunk;
 #pragma unroll
-        for (int i = 0; i < NB; ++i)
-            vb[i] = (min(ln0 + (NW * i + wave) * 16 + drow, g.N - 1) - ln0) * (int)g.ldwq + dchunk;
+        for (int i = 0; i < NB; ++i) {
+            if constexpr (W4) {   // 32 rows x 32 bytes per load: lane l fills half (l & 1) of row (l >> 1) with the
+                const int wrow = lane >> 1;                    // global half (l & 1) ^ bit 3 of the row (read-side bank spread)
+                vb[i] = (min(ln0 + (NW * i + wave) * 32 + wrow, g.N - 1) - ln0) * (int)g.ldwq + (((lane & 1) ^ ((wrow >> 3) & 1)) << 4);
+            } else {
+                vb[i] = (min(ln0 + (NW * i + wave) * 16 + drow, g.N - 1) - ln0) * (int)g.ldwq + dchunk;
+            }
+        }
     };
     auto issue = [&](int ktile, int stage) {
         unsigned char *sb = smem + stage * STG;
@@ -128,7 +145,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
             buffer_load_lds16(base_a, va[i], koff, sb + (NW * i + wave) * 1024);
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            buffer_load_lds16(base_b, vb[i], koff, sb + BM * BKD + (NW * i + wave) * 1024);
+            buffer_load_lds16(base_b, vb[i], W4 ? koff / 2 : koff, sb + BM * BKD + (NW * i + wave) * 1024);
     };
 
     // Scales and bias of a tile: global -> registers while the PREVIOUS tile's K loop runs, ->
@@ -140,8 +157,8 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
             const int e = tid + u * G::THREADS;
             float v = 0.f;
             if (e < BM) v = g.s_x[min(sm0 + e, g.M - 1)];
-            else if (e < BM + BN) v = g.s_n[min(sn0 + e - BM, g.N - 1)];
-            else if (e < BM + 2 * BN) v = g.s_o[min(sn0 + e - BM - BN, g.N - 1)];
+            else if (e < BM + BN) v = g.s_n[min(sn0 + e - BM, g.N - 1)] * (W4 ? 0.0625f : 1.0f);   // INT4 codes enter the MFMA
+            else if (e < BM + 2 * BN) v = g.s_o[min(sn0 + e - BM - BN, g.N - 1)] * (W4 ? 0.0625f : 1.0f);   // times 16 (exact)
             else if (e < BM + 3 * BN && g.bias) v = g.bias[min(sn0 + e - BM - 2 * BN, g.N - 1)];
             r_s[u] = v;
         }
@@ -158,16 +175,25 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
     // ---- fragment addressing --------------------------------------------------------------
     const int frow = lane & 31, fhalf = lane >> 5, fsw = swz64(frow);
     const int x_base = (wm * G::WTM + frow) * BKD;               // X rows: MFMA B operand
-    const int w_base = BM * BKD + (wn * G::WTN + frow) * BKD;    // W rows: MFMA A operand
+    // W rows: MFMA A operand.  Packed INT4: 32-byte rows, k-step ks in 16-byte half ks ^ bit 3 of the row, this
+    // lane's eight bytes at + 8 * fhalf.
+    const int w_base = W4 ? BM * BKD + (wn * G::WTN + frow) * 32 + 8 * fhalf : BM * BKD + (wn * G::WTN + frow) * BKD;
     int coff[2];
     coff[0] = ((0 | fhalf) ^ fsw) << 4;
     coff[1] = ((2 | fhalf) ^ fsw) << 4;
+    int wcoff[2];
+    wcoff[0] = W4 ? ((0 ^ ((frow >> 3) & 1)) << 4) : coff[0];
+    wcoff[1] = W4 ? ((1 ^ ((frow >> 3) & 1)) << 4) : coff[1];
+    auto read_w = [&](const unsigned char *sb, int j, int c) -> v4i {   // W fragment of block j, k-step offset c
+        if constexpr (W4) return unpack_w4(*reinterpret_cast<const v2i *>(sb + w_base + j * 32 * 32 + c));
+        else return *reinterpret_cast<const v4i *>(sb + w_base + j * 32 * BKD + c);
+    };
 
     v16i acc[TM][TN];
     v4i xf[2][TM], wf[2][TN];   // fragments of the two k-steps of a stage
     auto load_frags = [&](const unsigned char *sb, int ks) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) wf[ks][j] = *reinterpret_cast<const v4i *>(sb + w_base + j * 32 * BKD + coff[ks]);
+        for (int j = 0; j < TN; ++j) wf[ks][j] = read_w(sb, j, wcoff[ks]);
 #pragma unroll
         for (int i = 0; i < TM; ++i) xf[ks][i] = *reinterpret_cast<const v4i *>(sb + x_base + i * 32 * BKD + coff[ks]);
     };
@@ -382,13 +408,12 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
                         const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
                         const unsigned char *hb0 = smem + hstage0 * STG;
                         ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                            *reinterpret_cast<const v4i *>(hb0 + w_base + j * 32 * BKD + coff[0]),
+                            read_w(hb0, j, wcoff[0]),
                             *reinterpret_cast<const v4i *>(hb0 + x_base + i * 32 * BKD + coff[0]), zero, 0, 0, 0);
                         for (int s = 1; s < o_steps; ++s) {
                             const unsigned char *hb = smem + ((hstage0 + (s >> 1)) % NSTAGE) * STG;
-                            const int c = coff[s & 1];
-                            const v4i wo = *reinterpret_cast<const v4i *>(hb + w_base + j * 32 * BKD + c);
-                            const v4i xo = *reinterpret_cast<const v4i *>(hb + x_base + i * 32 * BKD + c);
+                            const v4i wo = read_w(hb, j, wcoff[s & 1]);
+                            const v4i xo = *reinterpret_cast<const v4i *>(hb + x_base + i * 32 * BKD + coff[s & 1]);
                             ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(wo, xo, ao, 0, 0, 0);
                         }
                     }
@@ -421,8 +446,9 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
                         if (m_lane < g.M && n + 4 <= g.N) {
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
-                                if (g.dbg_n) g.dbg_n[(size_t)m_lane * g.N + n + e] = acc[i][j][4 * q + e];
-                                if (g.dbg_o) g.dbg_o[(size_t)m_lane * g.N + n + e] = HASO ? ao[4 * q + e] : 0;
+                                // (INT4 codes were multiplied by 16 on the way in: the sums are exact multiples)
+                                if (g.dbg_n) g.dbg_n[(size_t)m_lane * g.N + n + e] = acc[i][j][4 * q + e] >> (W4 ? 4 : 0);
+                                if (g.dbg_o) g.dbg_o[(size_t)m_lane * g.N + n + e] = HASO ? ao[4 * q + e] >> (W4 ? 4 : 0) : 0;
                             }
                         }
                     }
@@ -482,11 +508,11 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE>::WAVES_P
 #endif
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool DBG, typename OutT>
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool DBG, typename OutT, bool W4>
 qarvd_status launch_one(const GemmArgs &g, hipStream_t st)
 {
-    using G = Geo<BM, BN, WM, WN, NSTAGE>;
-    auto k = gemm_dma_kernel<BM, BN, WM, WN, NSTAGE, DUAL, DBG, OutT>;
+    using G = Geo<BM, BN, WM, WN, NSTAGE, W4>;
+    auto k = gemm_dma_kernel<BM, BN, WM, WN, NSTAGE, DUAL, DBG, OutT, W4>;
     QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
     constexpr int LDS_PER_CU = 160 * 1024;
     const int wg_per_cu = std::max(1, std::min(LDS_PER_CU / G::LDS_BYTES, (G::WAVES_PER_EU * 4) / G::NW));
@@ -498,7 +524,7 @@ qarvd_status launch_one(const GemmArgs &g, hipStream_t st)
 
 }  // namespace
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool W4>
 qarvd_status launch_dma(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
 {
     GemmArgs g = g0;
@@ -506,20 +532,25 @@ qarvd_status launch_dma(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     g.tiles_n = (g.N + BN - 1) / BN;
     const bool dbg = g.dbg_n != nullptr || g.dbg_o != nullptr;   // raw-accumulator dumps: separate, slower build
     if (ydt == QARVD_BF16)
-        return !dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, uint16_t>(g, st)
-                    : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, uint16_t>(g, st);
-    return !dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, float>(g, st)
-                : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, float>(g, st);
+        return !dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, uint16_t, W4>(g, st)
+                    : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, uint16_t, W4>(g, st);
+    return !dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, float, W4>(g, st)
+                : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, float, W4>(g, st);
 }
 
-#define QARVD_INST(BM, BN, WM, WN, NS)                                                                      \
-    template qarvd_status launch_dma<BM, BN, WM, WN, NS, true>(const GemmArgs &, qarvd_dtype, hipStream_t); \
-    template qarvd_status launch_dma<BM, BN, WM, WN, NS, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
+#define QARVD_INST(BM, BN, WM, WN, NS)                                                                             \
+    template qarvd_status launch_dma<BM, BN, WM, WN, NS, true, false>(const GemmArgs &, qarvd_dtype, hipStream_t); \
+    template qarvd_status launch_dma<BM, BN, WM, WN, NS, false, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
+#define QARVD_INST_W4(BM, BN, WM, WN, NS)                                                                         \
+    template qarvd_status launch_dma<BM, BN, WM, WN, NS, true, true>(const GemmArgs &, qarvd_dtype, hipStream_t); \
+    template qarvd_status launch_dma<BM, BN, WM, WN, NS, false, true>(const GemmArgs &, qarvd_dtype, hipStream_t);
 QARVD_INST(256, 256, 2, 4, 4)
 QARVD_INST(256, 128, 4, 2, 4)
 QARVD_INST(128, 256, 2, 4, 4)
 QARVD_INST(256, 128, 2, 2, 3)
 QARVD_INST(192, 128, 2, 2, 3)
 QARVD_INST(128, 128, 2, 2, 4)
+QARVD_INST_W4(256, 256, 2, 4, 4)
+QARVD_INST_W4(128, 128, 2, 2, 4)
 
 }  // namespace qarvd_gemm

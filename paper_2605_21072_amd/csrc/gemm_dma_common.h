@@ -54,6 +54,11 @@ __device__ __forceinline__ void buffer_store16(void *base, int bytes, int voffse
     typedef unsigned int v4u_t __attribute__((ext_vector_type(4)));
     const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(base, 0, bytes, 0x00020000);
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u_t, data), r, voffset, soffset, 0);
+    // A 16-byte buffer store still reads its data registers in the cycle after it issues.  The compiler
+    // keeps that slot free of VALU writes to them only when the scalar offset is an immediate; with a
+    // register offset it let one through, and the first dword of some lanes went out overwritten
+    // (seen on MI355X as sporadic wrong outputs).  Hold the registers for two more wait states.
+    asm volatile("s_nop 1" : : "v"(data));
 #else
     (void)base; (void)bytes; (void)voffset; (void)soffset; (void)data;
 #endif

@@ -50,6 +50,15 @@ __device__ __forceinline__ int quantize_i8(float x, float s)
     return (int)r;
 }
 
+// The same quantizer with the symmetric range of another bit-width: q in [-qmax, qmax], qmax = 2^(b-1) - 1.
+__device__ __forceinline__ int quantize_sym(float x, float s, float qmax)
+{
+    if (s == 0.0f) return 0;
+    float r = rintf(x / s);
+    r = fminf(fmaxf(r, -qmax), qmax);
+    return (int)r;
+}
+
 // Same result as quantize_i8, without the ~10-instruction IEEE division on the common path.
 //   y' = x * rcp(s) is within |x/s| * 2^-22 <= 127 * 2^-22 < 4e-5 of the true quotient (|x/s| <= 127
 //   under an absmax scale; larger quotients only occur with a static scale and are far from any

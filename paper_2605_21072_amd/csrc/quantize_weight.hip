@@ -174,7 +174,8 @@ __global__ __launch_bounds__(1024) void build_perm_kernel(const uint8_t *__restr
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const float *__restrict__ W, int N, int K, int64_t ldw,
                                                             const int32_t *__restrict__ pos, const DetectScalars *sc,
                                                             int8_t *__restrict__ Wq, int64_t ldwq,
-                                                            float *__restrict__ s_normal, float *__restrict__ s_outlier)
+                                                            float *__restrict__ s_normal, float *__restrict__ s_outlier,
+                                                            float qmax)
 {
     __shared__ float red[8];
     const int j = blockIdx.x;
@@ -198,8 +199,8 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const float *__restr
     __syncthreads();
     a_o = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     a_n = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
-    const float so = a_o / 127.0f;
-    const float sn = a_n / 127.0f;
+    const float so = a_o / qmax;     // qmax = 127 (INT8 codes) or 7 (INT4 codes)
+    const float sn = a_n / qmax;
     if (tid == 0) {
         s_outlier[j] = so;
         s_normal[j] = sn;
@@ -207,11 +208,27 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const float *__restr
     int8_t *out = Wq + (size_t)j * ldwq;
     for (int k = tid; k < K; k += 256) {
         const int p = pos[k];
-        out[p] = (int8_t)quantize_i8(w[k], p < K_o ? so : sn);
+        out[p] = (int8_t)quantize_sym(w[k], p < K_o ? so : sn, qmax);
     }
     // zero padding: [K_o, n_off) and [n_off + K_n, kp)
     for (int p = K_o + tid; p < n_off; p += 256) out[p] = 0;
     for (int p = n_off + (K - K_o) + tid; p < kp; p += 256) out[p] = 0;
+}
+
+// INT4 packing: the codes of each aligned group of 16 packed positions g go into 8 bytes; byte i < 4
+// holds positions 16g+i (low nibble) and 16g+4+i (high nibble), byte 4+i positions 16g+8+i and
+// 16g+12+i.  (Shifting a packed dword left by 4 and masking 0xF0F0F0F0 then yields four consecutive
+// codes, each times 16, in byte order; masking the dword itself the next four.)
+__global__ __launch_bounds__(256) void pack_w4_kernel(const int8_t *__restrict__ codes, int64_t ldc, int N, int kp,
+                                                      uint8_t *__restrict__ Wq4, int64_t ldwq4)
+{
+    const int j = blockIdx.x;
+    const int b = blockIdx.y * 256 + threadIdx.x;      // output byte of the row
+    if (b >= kp / 2) return;
+    const int g = b >> 3, i = b & 7;
+    const int lo = 16 * g + (i < 4 ? i : 8 + (i - 4));
+    const int8_t *c = codes + (size_t)j * ldc;
+    Wq4[(size_t)j * ldwq4 + b] = (uint8_t)((c[lo] & 0xF) | ((c[lo + 4] & 0xF) << 4));
 }
 
 struct Workspace {
@@ -288,11 +305,14 @@ extern "C" size_t qarvd_quantize_weight_workspace(int32_t N, int32_t K)
     return carve(nullptr, K, nullptr);
 }
 
-extern "C" qarvd_status qarvd_quantize_weight(const float *W, int32_t N, int32_t K, int64_t ldw,
-                                              const qarvd_detect_cfg *cfg, int8_t *Wq, int64_t ldwq,
-                                              float *s_normal, float *s_outlier, int32_t *perm,
-                                              int32_t *K_o_host, float *v_out, void *workspace,
-                                              size_t workspace_bytes, void *stream)
+namespace {
+
+// bits = 8: Wq is the INT8 output [N, ldwq].  bits = 4: Wq is the packed INT4 output [N, ldwq bytes]; the
+// one-byte codes go to a temporary behind the detector's workspace and are packed by a second kernel.
+qarvd_status quantize_weight_impl(int bits, const float *W, int32_t N, int32_t K, int64_t ldw,
+                                  const qarvd_detect_cfg *cfg, void *Wq, int64_t ldwq, float *s_normal,
+                                  float *s_outlier, int32_t *perm, int32_t *K_o_host, float *v_out,
+                                  void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!W || !Wq || !s_normal || !s_outlier || !perm || !K_o_host) return QARVD_ERR_INVALID_ARG;
     if (N <= 0 || K <= 0 || K > QARVD_MAX_K || ldw < K) return QARVD_ERR_INVALID_ARG;
@@ -304,14 +324,19 @@ extern "C" qarvd_status qarvd_quantize_weight(const float *W, int32_t N, int32_t
     // produce: K rounded up to 128 when the aligned count is a multiple of 32 (no inner padding),
     // else the general worst case.
     const bool no_inner_pad = !c.forced_mask && (c.align % 32) == 0;
-    if (ldwq < (no_inner_pad ? qarvd_round_up(K, 128) : qarvd_packed_k(K, -1))) return QARVD_ERR_INVALID_ARG;
+    const int64_t kp_max = no_inner_pad ? qarvd_round_up(K, 128) : qarvd_packed_k(K, -1);
+    if (ldwq < (bits == 8 ? kp_max : kp_max / 2)) return QARVD_ERR_INVALID_ARG;
     if (!qarvd_aligned16(Wq) || (ldwq % 16) != 0 || (reinterpret_cast<uintptr_t>(W) & 3u)) return QARVD_ERR_UNSUPPORTED;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return QARVD_ERR_WORKSPACE;
-    if (workspace_bytes < qarvd_quantize_weight_workspace(N, K)) return QARVD_ERR_WORKSPACE;
+    const size_t ws_detect = carve(nullptr, K, nullptr);
+    const int64_t ld_codes = qarvd_packed_k(K, -1);
+    if (workspace_bytes < ws_detect + (bits == 4 ? (size_t)N * ld_codes : 0)) return QARVD_ERR_WORKSPACE;
 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     Workspace ws;
     carve(workspace, K, &ws);
+    int8_t *codes = bits == 8 ? reinterpret_cast<int8_t *>(Wq) : reinterpret_cast<int8_t *>(workspace) + ws_detect;
+    const int64_t ldc = bits == 8 ? ldwq : ld_codes;
     const int gK256 = (K + 255) / 256;
 
     hipLaunchKernelGGL(column_norm_kernel, dim3((K + 63) / 64), dim3(64), 0, st, W, N, K, ldw, ws.v);
@@ -327,8 +352,8 @@ extern "C" qarvd_status qarvd_quantize_weight(const float *W, int32_t N, int32_t
         hipLaunchKernelGGL(select_by_rank_kernel, dim3(gK256), dim3(256), 0, st, ws.rank, K, ws.sc, ws.sel);
     }
     hipLaunchKernelGGL(build_perm_kernel, dim3(1), dim3(1024), 0, st, ws.sel, K, ws.sc, c.forced_mask ? 1 : 0, perm, ws.pos);
-    hipLaunchKernelGGL(quantize_rows_kernel, dim3(N), dim3(256), 0, st, W, N, K, ldw, ws.pos, ws.sc, Wq, ldwq, s_normal,
-                       s_outlier);
+    hipLaunchKernelGGL(quantize_rows_kernel, dim3(N), dim3(256), 0, st, W, N, K, ldw, ws.pos, ws.sc, codes, ldc, s_normal,
+                       s_outlier, bits == 8 ? 127.0f : 7.0f);
     if (v_out) QARVD_HIP_TRY(hipMemcpyAsync(v_out, ws.v, (size_t)K * 4, hipMemcpyDeviceToDevice, st));
     qarvd_status ls = qarvd_launch_status();
     if (ls != QARVD_OK) return ls;
@@ -336,5 +361,41 @@ extern "C" qarvd_status qarvd_quantize_weight(const float *W, int32_t N, int32_t
     QARVD_HIP_TRY(hipMemcpyAsync(&host_sc, ws.sc, sizeof(host_sc), hipMemcpyDeviceToHost, st));
     QARVD_HIP_TRY(hipStreamSynchronize(st));
     *K_o_host = host_sc.K_o;
+    if (bits == 4) {    // the packed extent depends on K_o, which is known on the host only now
+        const int kp = qarvd_packed(K, host_sc.K_o).kp;
+        hipLaunchKernelGGL(pack_w4_kernel, dim3(N, (kp / 2 + 255) / 256), dim3(256), 0, st, codes, ldc, N, kp,
+                           reinterpret_cast<uint8_t *>(Wq), ldwq);
+        ls = qarvd_launch_status();
+        if (ls != QARVD_OK) return ls;
+        QARVD_HIP_TRY(hipStreamSynchronize(st));   // the temporary lives in the caller's workspace
+    }
     return QARVD_OK;
+}
+
+}  // namespace
+
+extern "C" qarvd_status qarvd_quantize_weight(const float *W, int32_t N, int32_t K, int64_t ldw,
+                                              const qarvd_detect_cfg *cfg, int8_t *Wq, int64_t ldwq,
+                                              float *s_normal, float *s_outlier, int32_t *perm,
+                                              int32_t *K_o_host, float *v_out, void *workspace,
+                                              size_t workspace_bytes, void *stream)
+{
+    return quantize_weight_impl(8, W, N, K, ldw, cfg, Wq, ldwq, s_normal, s_outlier, perm, K_o_host, v_out, workspace,
+                                workspace_bytes, stream);
+}
+
+extern "C" size_t qarvd_quantize_weight_w4_workspace(int32_t N, int32_t K)
+{
+    if (N <= 0 || K <= 0 || K > QARVD_MAX_K) return 0;
+    return carve(nullptr, K, nullptr) + (size_t)N * qarvd_packed_k(K, -1);
+}
+
+extern "C" qarvd_status qarvd_quantize_weight_w4(const float *W, int32_t N, int32_t K, int64_t ldw,
+                                                 const qarvd_detect_cfg *cfg, uint8_t *Wq4, int64_t ldwq4,
+                                                 float *s_normal, float *s_outlier, int32_t *perm,
+                                                 int32_t *K_o_host, float *v_out, void *workspace,
+                                                 size_t workspace_bytes, void *stream)
+{
+    return quantize_weight_impl(4, W, N, K, ldw, cfg, Wq4, ldwq4, s_normal, s_outlier, perm, K_o_host, v_out, workspace,
+                                workspace_bytes, stream);
 }

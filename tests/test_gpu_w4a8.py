@@ -1,0 +1,176 @@
+"""GPU parity of the W4A8 path (packed INT4 dual-scale weights) against the oracle at bits = 4.
+
+Codes, scales, permutation, both INT32 accumulators: bit-exact.  Outputs: bf16 within 1 ulp, fp32
+within 1e-6 relative (observed: bit-equal, the epilogue is the same fixed fp32 sequence).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+q = pytest.importorskip("paper_2605_21072_amd")
+from gpu_util import bf16_bits, bf16_ulp_distance, dev, gpu_quantize_weight  # noqa: E402
+
+
+def pack_int8(a, K, K_o):
+    n_off, kp = q.packed_normal_offset(K_o), q.packed_k(K, K_o)
+    out = np.zeros((a.shape[0], kp), np.int8)
+    out[:, :K_o] = a[:, :K_o]
+    out[:, n_off:n_off + K - K_o] = a[:, K_o:]
+    return out
+
+
+def pack_int4(codes_packed):
+    """The documented INT4 layout, written independently of the library: groups of 16 positions in 8 bytes,
+    byte i < 4 = positions (i, 4+i), byte 4+i = positions (8+i, 12+i), low nibble first."""
+    n, kp = codes_packed.shape
+    g = codes_packed.reshape(n, kp // 16, 16).astype(np.uint8) & 0xF
+    out = np.empty((n, kp // 16, 8), np.uint8)
+    for i in range(4):
+        out[:, :, i] = g[:, :, i] | (g[:, :, 4 + i] << 4)
+        out[:, :, 4 + i] = g[:, :, 8 + i] | (g[:, :, 12 + i] << 4)
+    return out.reshape(n, kp // 2)
+
+
+def check_y(Y_gpu, ref):
+    if Y_gpu.dtype == torch.float32:
+        y, r = Y_gpu.cpu().numpy(), ref["Y_f32"]
+        rel = np.abs(y - r) / np.maximum(np.abs(r), 1e-30)
+        assert np.all((rel <= 1e-6) | (y == r)), "fp32 output beyond 1e-6 relative"
+        return int(np.count_nonzero(y.view(np.uint32) != r.view(np.uint32)))
+    d = bf16_ulp_distance(bf16_bits(Y_gpu), ref["Y_bf16"])
+    assert d.max() <= 1, "bf16 output beyond 1 ulp"
+    return int(np.count_nonzero(d))
+
+
+@pytest.mark.parametrize("seed,N,K,c", [(0, 64, 128, 3), (1, 300, 320, 20), (2, 257, 1000, 9), (3, 96, 37, 0),
+                                        (4, 1536, 1536, 8)])
+def test_quantize_weight_w4_matches_oracle(seed, N, K, c):
+    L = wl.small_random_case(4000 + seed, 4, N, K, c)
+    o = oracle.quantize_weight(L["W"], bits=4)
+    w = gpu_quantize_weight(L["W"], bits=4)
+    assert w.bits == 4 and w.K_o == o["K_o"]
+    assert np.array_equal(w.perm.cpu().numpy(), o["perm"])
+    assert np.array_equal(w.s_normal.cpu().numpy().view(np.uint32), o["s_normal"].view(np.uint32))
+    assert np.array_equal(w.s_outlier.cpu().numpy().view(np.uint32), o["s_outlier"].view(np.uint32))
+    assert np.array_equal(w.v.cpu().numpy().view(np.uint32), o["v"].view(np.uint32))
+    # the packed bytes are exactly the documented layout of the oracle's codes (padding nibbles zero)
+    expect = pack_int4(pack_int8(o["Wq"], K, o["K_o"]))
+    got = w.Wq.cpu().numpy()[:, :expect.shape[1]]
+    assert np.array_equal(got, expect)
+    assert np.array_equal(w.logical_Wq().cpu().numpy(), o["Wq"])
+
+
+def test_quantize_weight_w4_forced_masks_and_errors():
+    L = wl.small_random_case(4100, 4, 40, 96, 0)
+    for mask in (np.zeros(96, np.uint8), np.ones(96, np.uint8), (np.arange(96) % 5 == 0).astype(np.uint8)):
+        o = oracle.quantize_weight(L["W"], forced_mask=mask, bits=4)
+        w = gpu_quantize_weight(L["W"], forced_mask=mask, bits=4)
+        assert w.K_o == o["K_o"] == int(mask.sum())
+        assert np.array_equal(w.logical_Wq().cpu().numpy(), o["Wq"])
+    with pytest.raises(q.QarvdError):
+        gpu_quantize_weight(L["W"], bits=4, ldwq=16)          # row stride too small
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("M,N,K,K_o", [(300, 200, 384, 32), (520, 384, 1536, 64), (257, 136, 640, 0),
+                                       (64, 96, 130, 7), (33, 40, 96, 96), (700, 520, 512, 128)])
+def test_w4a8_gemm_accumulators_and_outputs(variant, M, N, K, K_o):
+    rng = np.random.default_rng(variant * 31 + M + N + K + K_o)
+    Xq = rng.integers(-127, 128, (M, K)).astype(np.int8)
+    Wq = rng.integers(-7, 8, (N, K)).astype(np.int8)
+    sx = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    sn = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    so = rng.uniform(0.01, 0.1, N).astype(np.float32)
+    b = rng.standard_normal(N).astype(np.float32)
+    ref = oracle.dual_gemm(Xq, sx, Wq, sn, so, b, K_o)
+    w = q.DualScaleWeight(dev(pack_int4(pack_int8(Wq, K, K_o))), dev(sn), dev(so), None, K_o, N, K, None, 4)
+    Xq_d = dev(pack_int8(Xq, K, K_o))
+    for out_dtype in (torch.float32, torch.bfloat16):
+        Y, an, ao = q.w8a8_dual_gemm(Xq_d, dev(sx), w, dev(b), M, out_dtype, debug_acc=True, variant=variant)
+        torch.cuda.synchronize()
+        assert np.array_equal(an.cpu().numpy(), ref["acc_n"])
+        assert np.array_equal(ao.cpu().numpy(), ref["acc_o"])
+        assert check_y(Y, ref) == 0
+        Y2 = q.w8a8_dual_gemm(Xq_d, dev(sx), w, dev(b), M, out_dtype, variant=variant)     # the timed path
+        torch.cuda.synchronize()
+        assert torch.equal(Y2.view(torch.int32 if out_dtype == torch.float32 else torch.int16),
+                           Y.view(torch.int32 if out_dtype == torch.float32 else torch.int16))
+
+
+def test_w4a8_extreme_accumulators():
+    M, N, K, K_o = 64, 64, 3072, 32
+    Xq = np.full((M, K), 127, np.int8)
+    Xq[1::2] = -127
+    Wq = np.full((N, K), -7, np.int8)
+    Wq[::2] = 7
+    one_m, one_n = np.ones(M, np.float32), np.ones(N, np.float32)
+    ref = oracle.dual_gemm(Xq, one_m, Wq, one_n, one_n, None, K_o)
+    w = q.DualScaleWeight(dev(pack_int4(pack_int8(Wq, K, K_o))), dev(one_n), dev(one_n), None, K_o, N, K, None, 4)
+    Y, an, ao = q.w8a8_dual_gemm(dev(pack_int8(Xq, K, K_o)), dev(one_m), w, None, M, torch.float32, debug_acc=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(an.cpu().numpy(), ref["acc_n"]) and np.array_equal(ao.cpu().numpy(), ref["acc_o"])
+    assert abs(int(ref["acc_n"][0, 0])) == 127 * 7 * 3040
+    assert check_y(Y, ref) == 0
+
+
+def test_w4a8_unsupported_shapes_are_refused():
+    M, N, K, K_o = 32, 44, 256, 0                      # N % 8 != 0: no fast path for INT4 weights
+    w = q.DualScaleWeight(torch.zeros((N, 128), dtype=torch.uint8, device="cuda"), torch.ones(N, device="cuda"),
+                          torch.ones(N, device="cuda"), None, K_o, N, K, None, 4)
+    with pytest.raises(q.QarvdError) as e:
+        q.w8a8_dual_gemm(torch.zeros((M, 256), dtype=torch.int8, device="cuda"), torch.ones(M, device="cuda"), w, None, M)
+    assert e.value.status == -2
+
+
+@pytest.mark.parametrize("layer,rows", [("cfg1.linear", None), (wl.TARGET_LAYER, 40), ("cfg2.ffn_down.c64", 40),
+                                        ("cfg4.M520.attn.c32", 40)])
+def test_w4a8_layers_end_to_end(layer, rows):
+    spec = wl.find_layer(layer)
+    L = wl.make_layer(spec)
+    o = oracle.quantize_weight(L["W"], bits=4)
+    w = gpu_quantize_weight(L["W"], bits=4)
+    assert np.array_equal(w.logical_Wq().cpu().numpy(), o["Wq"]) and w.K_o == o["K_o"]
+    Xq, sx = q.quant_act(dev(L["X"]), w.perm if w.K_o else None, w.K_o)
+    if rows is None:
+        sel = np.arange(spec.M)
+    else:
+        rng = np.random.default_rng(spec.seed + 4)
+        sel = np.unique(np.concatenate([[0, spec.M - 1], rng.choice(spec.M, rows - 2, replace=False)]))
+    Xq_o, sx_o = oracle.quant_act(L["X"][sel], o["perm"])
+    ref = oracle.dual_gemm(Xq_o, sx_o, o["Wq"], o["s_normal"], o["s_outlier"], L["bias"], o["K_o"])
+    st = torch.from_numpy(sel).cuda()
+    for variant in (0, 1, 2):
+        Y, an, ao = q.w8a8_dual_gemm(Xq, sx, w, dev(L["bias"]), spec.M, torch.bfloat16, debug_acc=True, variant=variant)
+        torch.cuda.synchronize()
+        assert np.array_equal(an[st].cpu().numpy(), ref["acc_n"])
+        assert np.array_equal(ao[st].cpu().numpy(), ref["acc_o"])
+        assert check_y(Y[st], ref) == 0
+
+
+@pytest.mark.parametrize("bits,variant", [(4, 1), (8, 11)])
+def test_repeated_launches_give_identical_fp32_outputs(bits, variant):
+    """Regression: 16-byte buffer stores followed at once by a write to their data registers lost the
+    first dword of some lanes now and then (fp32 output, 256x256 tile, outlier path).  Thirty launches
+    of that configuration must all equal the oracle bit for bit."""
+    M, N, K, K_o = 256, 256, 512, 128
+    rng = np.random.default_rng(5)
+    lim = 7 if bits == 4 else 127
+    Xq = rng.integers(-127, 128, (M, K)).astype(np.int8)
+    Wq = rng.integers(-lim, lim + 1, (N, K)).astype(np.int8)
+    sx = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    sn = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    so = rng.uniform(0.01, 0.1, N).astype(np.float32)
+    b = rng.standard_normal(N).astype(np.float32)
+    ref = oracle.dual_gemm(Xq, sx, Wq, sn, so, b, K_o)
+    packed = pack_int8(Wq, K, K_o)
+    w = q.DualScaleWeight(dev(pack_int4(packed) if bits == 4 else packed), dev(sn), dev(so), None, K_o, N, K, None, bits)
+    Xq_d, sx_d, b_d = dev(pack_int8(Xq, K, K_o)), dev(sx), dev(b)
+    for _ in range(30):
+        Y = q.w8a8_dual_gemm(Xq_d, sx_d, w, b_d, M, torch.float32, variant=variant)
+        torch.cuda.synchronize()
+        assert np.array_equal(Y.cpu().numpy().view(np.uint32), ref["Y_f32"].view(np.uint32))
