@@ -229,6 +229,27 @@ def main():
                                       note="register-resident v_mfma_i32_32x32x32_i8 loop on every CU, measured in this run")
     except Exception as e:  # diagnostic only
         out["mfma_issue_peak"] = dict(error=str(e))
+    if tgt:     # the same target layer with INT4 weights (W4A8, reported beside the headline; not part of `value`)
+        try:
+            lt = layers[tgt[len(tgt) // 2]]
+            w4 = q.quantize_weight(torch.from_numpy(wl.make_layer(lt["spec"])["W"]).to(dev), want_norms=False, bits=4)
+            Xq4, sx4 = q.quant_act(lt["X"], w4.perm if w4.K_o else None, w4.K_o)
+            for _ in range(5):
+                q.w8a8_dual_gemm(Xq4, sx4, w4, lt["bias"], lt["spec"].M, Y=lt["Y"])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                q.w8a8_dual_gemm(Xq4, sx4, w4, lt["bias"], lt["spec"].M, Y=lt["Y"])
+            e1.record()
+            torch.cuda.synchronize()
+            us4 = 1e3 * e0.elapsed_time(e1) / args.steps
+            out["w4a8_target_layer"] = dict(layer=lt["spec"].name, gemm_us=round(us4, 2),
+                                            gemm_tops=round(2.0 * lt["spec"].macs / us4 / 1e6, 1),
+                                            weight_bytes=int(w4.N * w4.kp // 2), int8_weight_bytes=int(w4.N * w4.kp),
+                                            note="back-to-back launches of qarvd_w4a8_dual_gemm on the target shape")
+            del w4, Xq4, sx4
+        except Exception as e:  # diagnostic only
+            out["w4a8_target_layer"] = dict(error=str(e))
     out["paper_context"] = "paper reports 1.30x end-to-end INT8 speedup and 1.97x size reduction on an NVIDIA A6000 " \
                            "with Triton kernels (whole pipeline, not this kernel)"
 
