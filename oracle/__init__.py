@@ -211,3 +211,27 @@ def linear(X, W, bias, tau=3.5, alpha=1.2, align=32, forced_mask=None):
     out.update(qw)
     out.update(Xq=Xq, s_x=sx)
     return out
+
+
+def gelu_tanh(x):
+    """Element-wise oracle_gelu_tanh on an fp32 array."""
+    x = _f32(x)
+    lib = _load()
+    lib.oracle_gelu_tanh.restype = C.c_float
+    lib.oracle_gelu_tanh.argtypes = [C.c_float]
+    return np.array([lib.oracle_gelu_tanh(float(v)) for v in x.ravel()], np.float32).reshape(x.shape)
+
+
+def dual_gemm_q8(Xq, s_x, Wq, s_normal, s_outlier, bias, K_o, s_out, act=0):
+    """Dual GEMM whose epilogue quantizes for the next layer.  Returns int8 [M, N]."""
+    Xq = np.ascontiguousarray(Xq, dtype=np.int8)
+    Wq = np.ascontiguousarray(Wq, dtype=np.int8)
+    M, K = Xq.shape
+    N = Wq.shape[0]
+    b = None if bias is None else _f32(bias)
+    Y8 = np.empty((M, N), np.int8)
+    _check(_load().oracle_dual_gemm_q8(_p(Xq, C.c_int8), _p(_f32(s_x), C.c_float), _p(Wq, C.c_int8),
+                                       _p(_f32(s_normal), C.c_float), _p(_f32(s_outlier), C.c_float),
+                                       _p(b, C.c_float), M, N, K, int(K_o), int(act), C.c_float(float(s_out)),
+                                       _p(Y8, C.c_int8)))
+    return Y8

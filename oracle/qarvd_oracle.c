@@ -407,6 +407,80 @@ int oracle_dual_gemm(const int8_t *Xq, const float *s_x, const int8_t *Wq, const
     return ORACLE_OK;
 }
 
+/* ----------- chained layers: the epilogue quantizes for the next layer (static scale) */
+
+/*
+ * GELU, tanh form, in fp32 with every operation spelled out so that any IEEE-754 machine gets the
+ * same bits:  gelu(x) = 0.5 x (1 + tanh(u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
+ *           = x * sigma(2u),                  sigma(z) = 1 / (1 + exp(-z)).
+ * exp(-z) = 2^t with t = -z log2(e) clamped to [-125, 125], split as n = rint(t), f = t - n in
+ * [-1/2, 1/2]; 2^f = exp(f ln 2) by its Taylor polynomial of degree 7 (relative error < 1e-8);
+ * the power of two goes into the exponent field.  The paper does not name the FFN activation; this is
+ * the one the Wan-style DiT blocks of Sec. 4.1 use, and the exact arithmetic is this build's choice.
+ */
+float oracle_gelu_tanh(float x)
+{
+    float x2, inner, z, t, n, f, g, p, e, sg;
+    union { float f; int32_t i; } u;
+    x2 = x * x;
+    inner = fmaf(0.0356774081f, x2, 0.7978845608f);
+    z = (x * inner) * 2.0f;
+    t = (-z) * 1.44269502f;
+    t = fminf(fmaxf(t, -125.0f), 125.0f);
+    n = rintf(t);
+    f = t - n;
+    g = f * 0.693147182f;
+    p = 1.0f / 5040.0f;
+    p = fmaf(p, g, 1.0f / 720.0f);
+    p = fmaf(p, g, 1.0f / 120.0f);
+    p = fmaf(p, g, 1.0f / 24.0f);
+    p = fmaf(p, g, 1.0f / 6.0f);
+    p = fmaf(p, g, 0.5f);
+    p = fmaf(p, g, 1.0f);
+    p = fmaf(p, g, 1.0f);
+    u.f = p;
+    u.i += (int32_t)n * (1 << 23);
+    e = u.f;
+    sg = 1.0f / (1.0f + e);
+    return x * sg;
+}
+
+/*
+ * The dual GEMM with the epilogue of a chained layer: the fp32 result r of oracle_dual_gemm
+ * (same three operations), optionally through the activation (act = 1: GELU above), is quantized
+ * with the NEXT layer's static per-tensor activation scale (Sec. 4.1 "per-tensor static
+ * quantization for activations"; Eq. (quantization)):  Y8 = clip(rint(a / s_out), -127, 127).
+ */
+int oracle_dual_gemm_q8(const int8_t *Xq, const float *s_x, const int8_t *Wq, const float *s_normal,
+                        const float *s_outlier, const float *bias, int M, int N, int K, int K_o,
+                        int act, float s_out, int8_t *Y8)
+{
+    if (!Xq || !s_x || !Wq || !s_normal || !s_outlier || !Y8 || M <= 0 || N <= 0 || K <= 0 || K_o < 0 ||
+        K_o > K || (act != 0 && act != 1) || !(s_out > 0.0f))
+        return ORACLE_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        for (int j = 0; j < N; ++j) {
+            const int8_t *x = Xq + (size_t)m * K;
+            const int8_t *w = Wq + (size_t)j * K;
+            int32_t acc_o = 0, acc_n = 0;
+            float b = bias ? bias[j] : 0.0f;
+            float r;
+            for (int p = 0; p < K_o; ++p)
+                acc_o += (int32_t)x[p] * (int32_t)w[p];
+            for (int p = K_o; p < K; ++p)
+                acc_n += (int32_t)x[p] * (int32_t)w[p];
+            r = (float)acc_o * s_outlier[j];
+            r = fmaf((float)acc_n, s_normal[j], r);
+            r = fmaf(r, s_x[m], b);
+            if (act == 1)
+                r = oracle_gelu_tanh(r);
+            Y8[(size_t)m * N + j] = quantize_sym(r, s_out, 127.0f);
+        }
+    }
+    return ORACLE_OK;
+}
+
 /* -------------------- independent single-scale W8A8 linear (invariant pin) */
 
 /*
