@@ -250,6 +250,66 @@ def main():
             del w4, Xq4, sx4
         except Exception as e:  # diagnostic only
             out["w4a8_target_layer"] = dict(error=str(e))
+    if tgt and args.config == 2:   # FFN pair with the INT8 hand-over in the up-projection's epilogue (beside the headline)
+        try:
+            up, down = wl.find_layer("cfg2.ffn_up.c16"), wl.find_layer("cfg2.ffn_down.c64")
+            Lu, Ld = wl.make_layer(up), wl.make_layer(down)
+            w2 = q.quantize_weight(torch.from_numpy(Ld["W"]).to(dev), want_norms=False)
+            cmap = q.packed_channel_map(w2)
+            W1 = torch.from_numpy(Lu["W"]).to(dev)
+            W1p = torch.zeros((cmap.numel(), up.K), dtype=torch.float32, device=dev)
+            b1p = torch.zeros(cmap.numel(), dtype=torch.float32, device=dev)
+            W1p[cmap >= 0] = W1[cmap[cmap >= 0]]
+            b1p[cmap >= 0] = torch.from_numpy(Lu["bias"]).to(dev)[cmap[cmap >= 0]]
+            w1 = q.quantize_weight(W1p, want_norms=False)
+            w1u = q.quantize_weight(W1, want_norms=False)
+            b1, b2 = torch.from_numpy(Lu["bias"]).to(dev), torch.from_numpy(Ld["bias"]).to(dev)
+            del W1, W1p
+            M = up.M
+            X = torch.from_numpy(Lu["X"]).to(dev).to(torch.bfloat16)
+            Xq1 = torch.empty((M, w1.kp), dtype=torch.int8, device=dev)
+            sx1 = torch.empty(M, dtype=torch.float32, device=dev)
+            H8 = torch.empty((M, w2.kp), dtype=torch.int8, device=dev)
+            Hb = torch.empty((M, up.N), dtype=torch.bfloat16, device=dev)
+            sx2 = torch.empty(M, dtype=torch.float32, device=dev)
+            Yf = torch.empty((M, down.N), dtype=torch.bfloat16, device=dev)
+            s_mid = 0.03
+            s_rows = torch.full((M,), s_mid, dtype=torch.float32, device=dev)
+
+            def chained():
+                q.quant_act(X, w1.perm if w1.K_o else None, w1.K_o, Xq=Xq1, s_x=sx1)
+                q.w8a8_dual_gemm_q8(Xq1, sx1, w1, b1p, M, s_mid, q.ACT_GELU_TANH, Y8=H8)
+                q.w8a8_dual_gemm(H8, s_rows, w2, b2, M, Y=Yf)
+
+            def separate():
+                q.quant_act(X, w1u.perm if w1u.K_o else None, w1u.K_o, Xq=Xq1, s_x=sx1)
+                q.w8a8_dual_gemm(Xq1, sx1, w1u, b1, M, Y=Hb)
+                g = torch.nn.functional.gelu(Hb, approximate="tanh")
+                q.quant_act(g, w2.perm if w2.K_o else None, w2.K_o, Xq=H8, s_x=sx2)
+                q.w8a8_dual_gemm(H8, sx2, w2, b2, M, Y=Yf)
+
+            def time_us(fn):
+                for _ in range(5):
+                    fn()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(args.steps):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                return 1e3 * e0.elapsed_time(e1) / args.steps
+
+            us_c, us_s = time_us(chained), time_us(separate)
+            ops = 2.0 * (up.macs + down.macs)
+            out["chained_ffn"] = dict(shape="M=4680, 1536 -> 8960 -> 1536", chained_us=round(us_c, 1),
+                                      separate_us=round(us_s, 1), speedup=round(us_s / us_c, 3),
+                                      chained_tops=round(ops / us_c / 1e6, 1),
+                                      note="chained: quant_act, up GEMM with GELU + static INT8 hand-over in its epilogue "
+                                           "(qarvd_w8a8_dual_gemm_q8), down GEMM; separate: quant_act, up GEMM to bf16, "
+                                           "an elementwise GELU kernel (torch), quant_act, down GEMM")
+            del w1, w1u, w2, X, Xq1, H8, Hb, Yf
+        except Exception as e:  # diagnostic only
+            out["chained_ffn"] = dict(error=str(e))
     out["paper_context"] = "paper reports 1.30x end-to-end INT8 speedup and 1.97x size reduction on an NVIDIA A6000 " \
                            "with Triton kernels (whole pipeline, not this kernel)"
 

@@ -195,6 +195,36 @@ qarvd_status qarvd_w4a8_dual_gemm(const int8_t *Xq, int64_t ldxq, const float *s
 int32_t qarvd_w4_gemm_num_variants(void);
 
 /*
+ * ONLINE GEMM + de-quantization for CHAINED layers (Sec. 4.1: activations are quantized per tensor
+ * with static, calibrated scales, so a layer can hand the next one INT8 codes directly; Eq.
+ * (quantization) applied to this layer's output with the next layer's scale):
+ *     y      = the fp32 result of qarvd_w8a8_dual_gemm (same epilogue arithmetic, bias included)
+ *     a      = y                          act = QARVD_ACT_NONE
+ *            = gelu_tanh(y) in fp32       act = QARVD_ACT_GELU_TANH:  y * sigma(2 sqrt(2/pi) (y + 0.044715 y^3)),
+ *              sigma(z) = 1 / (1 + 2^t), t = clamp(-z log2(e), -125, 125), 2^t = 2^rint(t) times the
+ *              degree-7 Taylor polynomial of exp((t - rint(t)) ln 2); every operation a single fp32
+ *              operation (fma where written as one), IEEE division
+ *     Y8[m,n] = clip(rint(a / out_scale), -127, 127), round-half-even
+ * Column n of Y8 is output row n of Wq: to feed the next layer without a separate pass, give THIS
+ * layer's weight rows (and bias) in the next layer's packed channel order, zero rows at its pad
+ * positions, so that N = qarvd_packed_k(K_next, K_o_next) and Y8 is that layer's Xq with
+ * s_x[m] = out_scale for every m.
+ *   Y8     out  device i8 [M, ldy8]; ldy8 >= N; columns >= N are not written
+ *   act, out_scale   out_scale in [1e-30, 1e30], else QARVD_ERR_INVALID_ARG
+ * Needs N % 16 == 0, Y8 16-byte aligned, ldy8 % 16 == 0, 16-byte aligned scales and bias and an
+ * outlier block of at most 128 packed bytes; otherwise QARVD_ERR_UNSUPPORTED.  Other arguments as
+ * qarvd_w8a8_dual_gemm.  variant: 0 = heuristic, 1..qarvd_q8_gemm_num_variants() pick a kernel.
+ * Fully asynchronous on `stream`.
+ */
+typedef enum { QARVD_ACT_NONE = 0, QARVD_ACT_GELU_TANH = 1 } qarvd_act;
+qarvd_status qarvd_w8a8_dual_gemm_q8(const int8_t *Xq, int64_t ldxq, const float *s_x,
+                                     const int8_t *Wq, int64_t ldwq, const float *s_normal,
+                                     const float *s_outlier, const float *bias, int32_t M, int32_t N,
+                                     int32_t K, int32_t K_o, qarvd_act act, float out_scale,
+                                     int8_t *Y8, int64_t ldy8, int32_t variant, void *stream);
+int32_t qarvd_q8_gemm_num_variants(void);
+
+/*
  * Same operation with the kernel variant chosen by the caller instead of the built-in
  * heuristic (variant 0 = heuristic).  qarvd_gemm_num_variants() is the count of selectable
  * variants (1..count); qarvd_gemm_variant_name(i) describes one.  A variant that cannot run

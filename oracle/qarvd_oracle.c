@@ -413,19 +413,20 @@ int oracle_dual_gemm(const int8_t *Xq, const float *s_x, const int8_t *Wq, const
  * GELU, tanh form, in fp32 with every operation spelled out so that any IEEE-754 machine gets the
  * same bits:  gelu(x) = 0.5 x (1 + tanh(u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
  *           = x * sigma(2u),                  sigma(z) = 1 / (1 + exp(-z)).
- * exp(-z) = 2^t with t = -z log2(e) clamped to [-125, 125], split as n = rint(t), f = t - n in
- * [-1/2, 1/2]; 2^f = exp(f ln 2) by its Taylor polynomial of degree 7 (relative error < 1e-8);
+ * exp(-z) = 2^t with t = -z log2(e) = x (C0 + C1 x^2), C0 = -2 log2(e) sqrt(2/pi), C1 = 0.044715 C0
+ * (the constants multiplied out in double, rounded once), clamped to [-125, 125], split as
+ * n = rint(t), f = t - n in [-1/2, 1/2]; 2^f = exp(f ln 2) by its Taylor polynomial of degree 7
+ * (relative error < 1e-8);
  * the power of two goes into the exponent field.  The paper does not name the FFN activation; this is
  * the one the Wan-style DiT blocks of Sec. 4.1 use, and the exact arithmetic is this build's choice.
  */
 float oracle_gelu_tanh(float x)
 {
-    float x2, inner, z, t, n, f, g, p, e, sg;
+    float x2, inner, t, n, f, g, p, e, sg;
     union { float f; int32_t i; } u;
     x2 = x * x;
-    inner = fmaf(0.0356774081f, x2, 0.7978845608f);
-    z = (x * inner) * 2.0f;
-    t = (-z) * 1.44269502f;
+    inner = fmaf(-0.102943240f, x2, -2.30220820f);
+    t = x * inner;
     t = fminf(fmaxf(t, -125.0f), 125.0f);
     n = rintf(t);
     f = t - n;

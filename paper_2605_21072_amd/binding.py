@@ -77,6 +77,11 @@ def load_library():
     lib.qarvd_w4a8_dual_gemm.restype = C.c_int
     lib.qarvd_w4_gemm_num_variants.argtypes = []
     lib.qarvd_w4_gemm_num_variants.restype = i32
+    lib.qarvd_w8a8_dual_gemm_q8.argtypes = [vp, i64, vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, C.c_int, f32, vp, i64,
+                                            i32, vp]
+    lib.qarvd_w8a8_dual_gemm_q8.restype = C.c_int
+    lib.qarvd_q8_gemm_num_variants.argtypes = []
+    lib.qarvd_q8_gemm_num_variants.restype = i32
     lib.qarvd_gemm_num_variants.argtypes = []
     lib.qarvd_gemm_num_variants.restype = i32
     lib.qarvd_gemm_variant_name.argtypes = [i32]
@@ -276,6 +281,40 @@ def w8a8_dual_gemm(Xq: torch.Tensor, s_x: torch.Tensor, w: DualScaleWeight, bias
                                           _ptr(Y), _dt(Y), Y.stride(0), _ptr(an), _ptr(ao), _stream(stream))
     _check(st, "qarvd_w8a8_dual_gemm")
     return (Y, an, ao) if debug_acc else Y
+
+
+ACT_NONE, ACT_GELU_TANH = 0, 1
+
+
+def q8_gemm_num_variants() -> int:
+    return int(load_library().qarvd_q8_gemm_num_variants())
+
+
+def w8a8_dual_gemm_q8(Xq: torch.Tensor, s_x: torch.Tensor, w: DualScaleWeight, bias: Optional[torch.Tensor], M: int,
+                      out_scale: float, act: int = ACT_NONE, Y8: Optional[torch.Tensor] = None, variant: int = 0,
+                      stream=None) -> torch.Tensor:
+    """qarvd_w8a8_dual_gemm_q8: the dual GEMM with activation and the next layer's static-scale
+    quantization in its epilogue.  Returns Y8 int8 [M, >= N]."""
+    lib = load_library()
+    if w.bits != 8:
+        raise ValueError("the chained epilogue takes INT8 weights")
+    if Y8 is None:
+        Y8 = torch.empty((M, w.N), dtype=torch.int8, device=Xq.device)
+    st = lib.qarvd_w8a8_dual_gemm_q8(_ptr(Xq), Xq.stride(0), _ptr(s_x), _ptr(w.Wq), w.Wq.stride(0), _ptr(w.s_normal),
+                                     _ptr(w.s_outlier), _ptr(bias), M, w.N, w.K, w.K_o, int(act), C.c_float(out_scale),
+                                     _ptr(Y8), Y8.stride(0), variant, _stream(stream))
+    _check(st, "qarvd_w8a8_dual_gemm_q8")
+    return Y8
+
+
+def packed_channel_map(w: DualScaleWeight) -> torch.Tensor:
+    """int64 [kp]: the input channel each packed position of `w` holds, -1 at pad positions.  A producing
+    layer whose weight rows are gathered with this map (zero rows at -1) emits `w`'s Xq directly."""
+    m = torch.full((w.kp,), -1, dtype=torch.int64, device=w.perm.device)
+    p = w.perm.to(torch.int64)
+    m[:w.K_o] = p[:w.K_o]
+    m[w.n_off:w.n_off + w.K - w.K_o] = p[w.K_o:]
+    return m
 
 
 def w8a8_linear(X: torch.Tensor, w: DualScaleWeight, bias: Optional[torch.Tensor], out_dtype=torch.bfloat16,

@@ -115,7 +115,7 @@ extern "C" qarvd_status qarvd_w8a8_dual_gemm_variant(int32_t variant, const int8
     g.Xq = Xq; g.Wq = Wq; g.s_x = s_x; g.s_n = s_normal; g.s_o = s_outlier; g.bias = bias;
     g.Y = Y; g.dbg_n = dbg_acc_normal; g.dbg_o = dbg_acc_outlier;
     g.ldxq = ldxq; g.ldwq = ldwq; g.ldy = ldy; g.M = M; g.N = N; g.n_off = pk.n_off; g.kp = pk.kp;
-    g.tiles_m = g.tiles_n = 0;
+    g.tiles_m = g.tiles_n = 0; g.act = 0; g.out_scale = 0.0f;
     if (variant == 0) variant = pick_variant(g, ydt);
     const Variant &v = kVariants[variant - 1];
     if (!variant_fits(v, g, ydt)) return QARVD_ERR_UNSUPPORTED;
@@ -172,7 +172,7 @@ extern "C" qarvd_status qarvd_w4a8_dual_gemm(const int8_t *Xq, int64_t ldxq, con
     g.Xq = Xq; g.Wq = reinterpret_cast<const int8_t *>(Wq4); g.s_x = s_x; g.s_n = s_normal; g.s_o = s_outlier; g.bias = bias;
     g.Y = Y; g.dbg_n = dbg_acc_normal; g.dbg_o = dbg_acc_outlier;
     g.ldxq = ldxq; g.ldwq = ldwq4; g.ldy = ldy; g.M = M; g.N = N; g.n_off = pk.n_off; g.kp = pk.kp;
-    g.tiles_m = g.tiles_n = 0;
+    g.tiles_m = g.tiles_n = 0; g.act = 0; g.out_scale = 0.0f;
     if (g.n_off > 128 || !vector_out_ok(g, ydt)) return QARVD_ERR_UNSUPPORTED;
     if (variant == 0) {     // same cost model as the INT8 path, restricted to the two tiles built for INT4
         const double T = g.kp / 64;
@@ -183,4 +183,62 @@ extern "C" qarvd_status qarvd_w4a8_dual_gemm(const int8_t *Xq, int64_t ldxq, con
     }
     const W4Variant &v = kW4Variants[variant - 1];
     return (g.n_off > 0 ? v.dual : v.single)(g, ydt, reinterpret_cast<hipStream_t>(stream));
+}
+
+// ---- chained layers: INT8 output quantized in the epilogue ----------------------------------------------
+namespace {
+struct Q8Variant {
+    int BM, BN;
+    double c, a, b;     // cost model of pick_variant
+    qarvd_status (*dual)(const GemmArgs &, hipStream_t);
+    qarvd_status (*single)(const GemmArgs &, hipStream_t);
+};
+const Q8Variant kQ8Variants[] = {
+    {256, 256, 2.2, 8.9, 0.688, launch_dma_q8<256, 256, 2, 4, 4, true>, launch_dma_q8<256, 256, 2, 4, 4, false>},
+    {128, 256, 5.0, 2.75, 0.490, launch_dma_q8<128, 256, 2, 4, 4, true>, launch_dma_q8<128, 256, 2, 4, 4, false>},
+    {128, 128, 2.0, 1.5, 0.309, launch_dma_q8<128, 128, 2, 2, 4, true>, launch_dma_q8<128, 128, 2, 2, 4, false>},
+};
+constexpr int kNumQ8Variants = sizeof(kQ8Variants) / sizeof(kQ8Variants[0]);
+}  // namespace
+
+extern "C" int32_t qarvd_q8_gemm_num_variants(void) { return kNumQ8Variants; }
+
+extern "C" qarvd_status qarvd_w8a8_dual_gemm_q8(const int8_t *Xq, int64_t ldxq, const float *s_x, const int8_t *Wq,
+                                                int64_t ldwq, const float *s_normal, const float *s_outlier,
+                                                const float *bias, int32_t M, int32_t N, int32_t K, int32_t K_o,
+                                                qarvd_act act, float out_scale, int8_t *Y8, int64_t ldy8,
+                                                int32_t variant, void *stream)
+{
+    if (!Xq || !Wq || !s_x || !s_normal || !s_outlier || !Y8) return QARVD_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0 || K <= 0 || K > QARVD_MAX_K || K_o < 0 || K_o > K) return QARVD_ERR_INVALID_ARG;
+    if (act != QARVD_ACT_NONE && act != QARVD_ACT_GELU_TANH) return QARVD_ERR_INVALID_ARG;
+    if (!(out_scale >= 1.0e-30f) || out_scale > 1.0e30f) return QARVD_ERR_INVALID_ARG;     // NaN, zero, negative, inf; 1 / s must be normal
+    if (variant < 0 || variant > kNumQ8Variants) return QARVD_ERR_INVALID_ARG;
+    const PackedK pk = qarvd_packed(K, K_o);
+    if (ldxq < pk.kp || ldwq < pk.kp || ldy8 < N) return QARVD_ERR_INVALID_ARG;
+    if (!qarvd_aligned16(Xq) || !qarvd_aligned16(Wq) || (ldxq % 16) || (ldwq % 16)) return QARVD_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(s_x) & 3u) || !qarvd_aligned16(s_normal) || !qarvd_aligned16(s_outlier) ||
+        !qarvd_aligned16(bias))
+        return QARVD_ERR_UNSUPPORTED;
+    // 16 codes per store; 32-bit byte offsets inside a tile
+    if ((N % 16) || !qarvd_aligned16(Y8) || (ldy8 % 16) || ldxq > (1 << 22) || ldwq > (1 << 22) || ldy8 > (1 << 22))
+        return QARVD_ERR_UNSUPPORTED;
+    GemmArgs g;
+    g.Xq = Xq; g.Wq = Wq; g.s_x = s_x; g.s_n = s_normal; g.s_o = s_outlier; g.bias = bias;
+    g.Y = Y8; g.dbg_n = nullptr; g.dbg_o = nullptr;
+    g.ldxq = ldxq; g.ldwq = ldwq; g.ldy = ldy8; g.M = M; g.N = N; g.n_off = pk.n_off; g.kp = pk.kp;
+    g.tiles_m = g.tiles_n = 0; g.act = (int32_t)act; g.out_scale = out_scale;
+    if (g.n_off > 128) return QARVD_ERR_UNSUPPORTED;
+    if (variant == 0) {
+        const double T = g.kp / 64;
+        double best_cost = 1e300;
+        for (int i = 0; i < kNumQ8Variants; ++i) {
+            const Q8Variant &c = kQ8Variants[i];
+            const long tiles = (long)((M + c.BM - 1) / c.BM) * ((N + c.BN - 1) / c.BN);
+            const double cost = c.c + (double)((tiles + 255) / 256) * (c.a + c.b * T);
+            if (cost < best_cost) { best_cost = cost; variant = i + 1; }
+        }
+    }
+    const Q8Variant &v = kQ8Variants[variant - 1];
+    return (g.n_off > 0 ? v.dual : v.single)(g, reinterpret_cast<hipStream_t>(stream));
 }

@@ -37,6 +37,10 @@ struct GemmArgs {
     int32_t n_off;     // first byte of the normal block (multiple of 32)
     int32_t kp;        // packed extent (multiple of 128)
     int32_t tiles_m, tiles_n;
+    // chained layers (INT8 output for the next layer): activation applied to the fp32 result and the
+    // next layer's static activation scale; unused for fp32 / bf16 outputs
+    int32_t act;
+    float out_scale;
 };
 
 // LDS image of an operand tile: row r at byte r*128, its eight 16-byte chunks XOR-swizzled by
@@ -82,6 +86,8 @@ template <int BM, int BN, int WM, int WN, bool DUAL>
 qarvd_status launch_staged(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool W4 = false>   // W4: Wq is packed INT4, ldwq in bytes
 qarvd_status launch_dma(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>   // INT8 output quantized in the epilogue
+qarvd_status launch_dma_q8(const GemmArgs &g, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
 qarvd_status launch_mfma16(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 

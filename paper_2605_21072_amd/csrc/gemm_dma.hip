@@ -389,6 +389,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
         }
     };
     const bool has_o = DUAL && o_steps > 0;
+    const float out_rscale = sizeof(OutT) == 1 ? 1.0f / g.out_scale : 0.0f;     // IEEE division: RN(1 / s)
 
     // the whole epilogue exists twice: with the outlier sum (HASO) and without it (a layer with no
     // outlier channels run through the dual kernel, or the single-accumulator build)
@@ -461,7 +462,14 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
                         wait_vmcnt<0>();
                         __builtin_amdgcn_sched_barrier(0);
                     }
-                    if constexpr (sizeof(OutT) == 2) {
+                    if constexpr (sizeof(OutT) == 1) {
+                        // chained layer: activation, then the next layer's static scale (Eq. (quantization)); two
+                        // blocks of 32 INT8 columns share a 64-byte patch row
+                        static_assert(sizeof(OutT) != 1 || TN % 2 == 0, "INT8 output pairs the column blocks");
+                        const unsigned pk = quantize4_static(y, g.act == 1, g.out_scale, out_rscale);
+                        const int c = 2 * (j & 1) + (q >> 1);
+                        *reinterpret_cast<unsigned *>(patch + frow * PATCH_RS + ((c ^ pswz) << 4) + 8 * (q & 1) + 4 * fhalf) = pk;
+                    } else if constexpr (sizeof(OutT) == 2) {
                         v2u pk;
                         pk.x = cvt_pk_bf16(y[0], y[1]);
                         pk.y = cvt_pk_bf16(y[2], y[3]);
@@ -474,6 +482,9 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
                 }
             }
             if constexpr (sizeof(OutT) == 2) flush_patch(i, j * 32);
+            if constexpr (sizeof(OutT) == 1) {
+                if (j & 1) flush_patch(i, (j - 1) * 32);
+            }
         }
     }
     };
@@ -537,6 +548,22 @@ qarvd_status launch_dma(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     return !dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, float, W4>(g, st)
                 : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, true, float, W4>(g, st);
 }
+
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
+qarvd_status launch_dma_q8(const GemmArgs &g0, hipStream_t st)
+{
+    GemmArgs g = g0;
+    g.tiles_m = (g.M + BM - 1) / BM;
+    g.tiles_n = (g.N + BN - 1) / BN;
+    return launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, int8_t, false>(g, st);
+}
+
+#define QARVD_INST_Q8(BM, BN, WM, WN, NS)                                                     \
+    template qarvd_status launch_dma_q8<BM, BN, WM, WN, NS, true>(const GemmArgs &, hipStream_t); \
+    template qarvd_status launch_dma_q8<BM, BN, WM, WN, NS, false>(const GemmArgs &, hipStream_t);
+QARVD_INST_Q8(256, 256, 2, 4, 4)
+QARVD_INST_Q8(128, 256, 2, 4, 4)
+QARVD_INST_Q8(128, 128, 2, 2, 4)
 
 #define QARVD_INST(BM, BN, WM, WN, NS)                                                                             \
     template qarvd_status launch_dma<BM, BN, WM, WN, NS, true, false>(const GemmArgs &, qarvd_dtype, hipStream_t); \

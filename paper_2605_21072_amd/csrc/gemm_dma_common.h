@@ -64,6 +64,85 @@ __device__ __forceinline__ void buffer_store16(void *base, int bytes, int voffse
 #endif
 }
 
+// ---- chained-layer epilogue: activation, then the next layer's static-scale INT8 code ---------------------
+// GELU, tanh form, in fp32 with every operation spelled out (the sequence the CPU reference of the
+// chained-layer epilogue defines, so both sides get the same bits and hence the same INT8 codes):
+//   gelu(x) = x * sigma(2u),  u = sqrt(2/pi) (x + 0.044715 x^3),  sigma(z) = 1 / (1 + exp(-z)),
+//   exp(-z) = 2^t,  t = x (C0 + C1 x^2) clamped to [-125, 125]  (C0 = -2 log2(e) sqrt(2/pi), C1 = 0.044715 C0),
+//   n = rint(t), 2^(t-n) by the degree-7 Taylor polynomial of exp((t-n) ln 2), n added into the exponent
+//   field; IEEE division.
+__device__ __forceinline__ float gelu_exponent(float x)       // t above: shared by the exact and the fast path
+{
+    const float x2 = x * x;
+    const float inner = fmaf(-0.102943240f, x2, -2.30220820f);
+    const float t = x * inner;
+    return fminf(fmaxf(t, -125.0f), 125.0f);
+}
+
+__device__ __forceinline__ float gelu_tanh_exact(float x, float t)
+{
+    const float n = rintf(t);
+    const float f = t - n;
+    const float g = f * 0.693147182f;
+    float p = 1.0f / 5040.0f;
+    p = fmaf(p, g, 1.0f / 720.0f);
+    p = fmaf(p, g, 1.0f / 120.0f);
+    p = fmaf(p, g, 1.0f / 24.0f);
+    p = fmaf(p, g, 1.0f / 6.0f);
+    p = fmaf(p, g, 0.5f);
+    p = fmaf(p, g, 1.0f);
+    p = fmaf(p, g, 1.0f);
+    const float e = __int_as_float(__float_as_int(p) + (int)n * (1 << 23));
+    const float sg = 1.0f / (1.0f + e);
+    return x * sg;
+}
+
+// Four fp32 results -> four INT8 codes in one dword (byte e = code of y[e]):
+//     code = clip(rint(a / s), -127, 127),  a = y or gelu(y) as defined above,  rs = RN(1 / s).
+// Common path, a handful of instructions per value: a~ from the hardware 2^t and reciprocal (each within
+// 1 ulp; t itself is the exact sequence's), q~ = a~ * rs, rounded by adding 1.5 * 2^23 (round-half-even, and
+// the code lands in the low byte of the sum).  How far q~ can be from the exact sequence's RN(a / s), while
+// |a / s| <= 127.5:   2^t and the polynomial differ by < 3.5e-7 relative, 1 + e, the reciprocal against the
+// division and the products add < 3.5e-7, rs and the last product < 1.8e-7: under 9e-7 relative, 1.2e-4 in
+// units of a code.  Beyond 127.5 both sides clip.  A value whose q~ is more than 5e-4 away from every
+// half-integer therefore rounds to the same code; the others (about 1 in 1000) take the exact sequence.
+__device__ __forceinline__ unsigned quantize4_static(const float (&y)[4], bool gelu, float s, float rs)
+{
+    constexpr float MAGIC = 12582912.0f;      // 1.5 * 2^23
+    float m[4];
+    unsigned redo = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float a = y[e];
+        if (gelu) {
+            const float t = gelu_exponent(y[e]);
+            a = y[e] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
+        }
+        const float qa = fminf(fmaxf(a * rs, -127.0f), 127.0f);
+        m[e] = qa + MAGIC;
+        const float r = m[e] - MAGIC;
+        redo |= (fabsf(qa - r) < 0.4995f) ? 0u : (1u << e);      // NaN lands here too
+    }
+    if (redo) {
+#pragma unroll 1
+        for (int e = 0; e < 4; ++e) {
+            if ((redo >> e) & 1u) {
+                const float x = e == 0 ? y[0] : e == 1 ? y[1] : e == 2 ? y[2] : y[3];
+                const float a = gelu ? gelu_tanh_exact(x, gelu_exponent(x)) : x;
+                const float me = (float)quantize_i8(a, s) + MAGIC;
+                m[0] = e == 0 ? me : m[0];
+                m[1] = e == 1 ? me : m[1];
+                m[2] = e == 2 ? me : m[2];
+                m[3] = e == 3 ? me : m[3];
+            }
+        }
+    }
+    // byte 0 of each sum, gathered: v_perm_b32 picks bytes 0..3 from its second operand, 4..7 from its first
+    const unsigned lo = __builtin_amdgcn_perm(__float_as_uint(m[1]), __float_as_uint(m[0]), 0x0c0c0400u);
+    const unsigned hi = __builtin_amdgcn_perm(__float_as_uint(m[3]), __float_as_uint(m[2]), 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
 // two fp32 -> packed bf16, round-to-nearest-even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b)
 {
