@@ -262,7 +262,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
         tile_coords(min(t, ntiles - 1), g.tiles_m, g.tiles_n, tm, tn);
         fetch_scales(tm * BM, tn * BN);
     };
-    long long p_vm = 0, p_bar = 0, p_loop = 0, p_epi = 0, p_pro = 0, p_mark = p_ts;
+    long long p_vm = 0, p_vmw = 0, p_bar = 0, p_loop = 0, p_epi = 0, p_pro = 0, p_mark = p_ts;
     int p_tiles = 0;
 
     for (;;) {
@@ -301,11 +301,9 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
     for (int it = 0; it < T - AHEAD; ++it) {     // steady state: every tile here is a normal tile
         const unsigned char *sb = smem + stage * STG;
         const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
-        // Each fragment set is waited for explicitly BEFORE the next set's reads are issued (it was
-        // read a whole k-step ago, so the wait is free); the MFMAs below then need no wait of their
-        // own and the reads just issued land underneath them.
-        wait_lgkmcnt0();
-        __builtin_amdgcn_sched_barrier(0);
+        // The fragments used here were read a half-iteration ago, one after each of the first MFMAs;
+        // the compiler's counted waits (lgkmcnt(n) just before the first MFMA that needs a fragment)
+        // give the last of them the longest time to land.
         load_frags(sb, 1);
         mma(0);
         interleave_reads();                      // MFMA, read, MFMA, read, ...: the MFMA pipe never drains
@@ -316,13 +314,11 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
         long long q1 = clock64();
         __builtin_amdgcn_s_barrier();
         long long q2 = clock64();
-        p_bar += q2 - q1; (void)q0;
+        p_bar += q2 - q1; p_vmw += q1 - q0;
 #else
         wait_vmcnt<(AHEAD - 2) * G::NLOAD>();
         __builtin_amdgcn_s_barrier();
 #endif
-        wait_lgkmcnt0();
-        __builtin_amdgcn_sched_barrier(0);
         load_frags(smem + nstage * STG, 0);
         issue(seq(it + AHEAD), stage >= 1 ? stage - 1 : NSTAGE - 1);   // stage (it + AHEAD) % NSTAGE
         mma(1);
@@ -379,114 +375,162 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
     const int y_bytes = (min(BM, g.M - m0) - 1) * ldy_b + g.N * ESZ;
     const int y_lane = (wm * G::WTM + (lane >> 2)) * ldy_b + (n0 + wn * G::WTN + (lane & 3) * EPC) * ESZ;
     const int n_left = g.N - n0 - wn * G::WTN - (lane & 3) * EPC;     // columns from this lane's chunk to the matrix edge
-    auto flush_patch = [&](int i, int col0) {          // col0: first column of the pass inside the wave tile
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int row = p * 16 + (lane >> 2), ch = lane & 3;
-            const v4i v = *reinterpret_cast<const v4i *>(patch + row * PATCH_RS + ((ch ^ ((row >> 2) & 3)) << 4));
-            const int voff = col0 + EPC <= n_left ? y_lane : 0x7ffffff0;
-            buffer_store16(y_tile, y_bytes, voff, (i * 32 + p * 16) * ldy_b + col0 * ESZ, v);
-        }
-    };
     const bool has_o = DUAL && o_steps > 0;
     const float out_rscale = sizeof(OutT) == 1 ? 1.0f / g.out_scale : 0.0f;     // IEEE division: RN(1 / s)
 
-    // the whole epilogue exists twice: with the outlier sum (HASO) and without it (a layer with no
-    // outlier channels run through the dual kernel, or the single-accumulator build)
+    // The epilogue is a chain of LDS round trips (scales in, patch out and back) around little arithmetic,
+    // so it is written as a software pipeline over its units of work, in program order:
+    //   * a patch is read back into registers as soon as it is complete, but stored to global memory only
+    //     after the NEXT unit's arithmetic (LDS operations of a wave execute in order, so the next unit's
+    //     patch writes cannot overtake that read);
+    //   * the outlier sums of the next block are started (MFMA) before the current block's arithmetic;
+    //   * the per-column scales and biases of a column block are loaded once, ahead of the row blocks that
+    //     use them (fp32 / bf16: column block outermost; INT8 pairs two column blocks in one 64-byte patch
+    //     row, so there the row block stays outermost and each block loads its columns' scales up front).
+    // The whole epilogue exists twice: with the outlier sum (HASO) and without it (a layer with no outlier
+    // channels run through the dual kernel, or the single-accumulator build).
     auto epilogue = [&](auto haso_tag) {
         constexpr bool HASO = decltype(haso_tag)::value;
+        constexpr bool J_OUTER = sizeof(OutT) != 1;
+        constexpr int NBLK = TM * TN;
+        auto blk_i = [&](int b) { return J_OUTER ? b % TM : b / TN; };
+        auto blk_j = [&](int b) { return J_OUTER ? b / TM : b % TN; };
+
+        v4i pend[2];
+        int pend_voff = 0, pend_soff = 0;
+        bool pending = false, stored = false;       // compile-time after unrolling
+        auto flush_commit = [&]() {                 // patch (already in registers) -> global
+            if (!pending) return;
+            if (!stored) {
+                // The next tile's first stages were issued when this epilogue began and have had a unit's
+                // arithmetic to land.  Waiting for them here, before the first output store is issued, means
+                // no later wait for a stage load ever has an output store ahead of it in the (in-order)
+                // memory counter.
+                __builtin_amdgcn_sched_barrier(0);
+                wait_vmcnt<0>();
+                __builtin_amdgcn_sched_barrier(0);
+                stored = true;
+            }
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int ml = wm * G::WTM + i * 32 + frow;
-        const int m_lane = m0 + ml;
-        const float sx = sx_lds[ml];
+            for (int p = 0; p < 2; ++p) buffer_store16(y_tile, y_bytes, pend_voff, pend_soff + p * 16 * ldy_b, pend[p]);
+            pending = false;
+        };
+        auto flush_issue = [&](int i, int col0) {   // col0: first column of the pass inside the wave tile
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            {
-                v16i ao;
-                {
-                    if constexpr (HASO) {   // first outlier k-step starts from a zero accumulator, the rest chain on it
-                        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                        const unsigned char *hb0 = smem + hstage0 * STG;
-                        ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                            read_w(hb0, j, wcoff[0]),
-                            *reinterpret_cast<const v4i *>(hb0 + x_base + i * 32 * BKD + coff[0]), zero, 0, 0, 0);
-                        for (int s = 1; s < o_steps; ++s) {
-                            const unsigned char *hb = smem + ((hstage0 + (s >> 1)) % NSTAGE) * STG;
-                            const v4i wo = read_w(hb, j, wcoff[s & 1]);
-                            const v4i xo = *reinterpret_cast<const v4i *>(hb + x_base + i * 32 * BKD + coff[s & 1]);
-                            ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(wo, xo, ao, 0, 0, 0);
-                        }
+            for (int p = 0; p < 2; ++p) {
+                const int row = p * 16 + (lane >> 2), ch = lane & 3;
+                pend[p] = *reinterpret_cast<const v4i *>(patch + row * PATCH_RS + ((ch ^ ((row >> 2) & 3)) << 4));
+            }
+            pend_voff = col0 + EPC <= n_left ? y_lane : 0x7ffffff0;
+            pend_soff = i * 32 * ldy_b + col0 * ESZ;
+            pending = true;
+        };
+        auto flush = [&](int i, int col0) {
+            flush_commit();
+            flush_issue(i, col0);
+        };
+        auto head_mma = [&](int i, int j) -> v16i {   // outlier sum of block (i, j): the first k-step starts from zero
+            const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            const unsigned char *hb0 = smem + hstage0 * STG;
+            v16i ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                read_w(hb0, j, wcoff[0]), *reinterpret_cast<const v4i *>(hb0 + x_base + i * 32 * BKD + coff[0]), zero, 0, 0, 0);
+            for (int s = 1; s < o_steps; ++s) {
+                const unsigned char *hb = smem + ((hstage0 + (s >> 1)) % NSTAGE) * STG;
+                const v4i wo = read_w(hb, j, wcoff[s & 1]);
+                const v4i xo = *reinterpret_cast<const v4i *>(hb + x_base + i * 32 * BKD + coff[s & 1]);
+                ao = __builtin_amdgcn_mfma_i32_32x32x32_i8(wo, xo, ao, 0, 0, 0);
+            }
+            return ao;
+        };
+
+        float sxr[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) sxr[i] = sx_lds[wm * G::WTM + i * 32 + frow];
+        v4f sn[4], so[4], bs[4];
+        auto load_cols = [&](int j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int nt = wn * G::WTN + j * 32 + 8 * q + 4 * fhalf;      // column inside the workgroup tile
+                sn[q] = *reinterpret_cast<const v4f *>(sn_lds + nt);
+                if constexpr (HASO) so[q] = *reinterpret_cast<const v4f *>(so_lds + nt);
+                bs[q] = *reinterpret_cast<const v4f *>(bs_lds + nt);
+            }
+        };
+        // (the look-ahead costs 16 registers; only the bf16 build, the one that is timed, has them to spare)
+        constexpr bool AO_AHEAD = HASO && sizeof(OutT) == 2 && !DBG && !W4;
+        v16i ao_next;
+        if constexpr (AO_AHEAD) ao_next = head_mma(blk_i(0), blk_j(0));
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+            const int i = blk_i(b), j = blk_j(b);
+            if (!J_OUTER || i == 0) load_cols(j);
+            v16i ao;
+            if constexpr (AO_AHEAD) {
+                ao = ao_next;
+                if (b + 1 < NBLK) ao_next = head_mma(blk_i(b + 1), blk_j(b + 1));
+            } else if constexpr (HASO) {
+                ao = head_mma(i, j);
+            }
+            const int m_lane = m0 + wm * G::WTM + i * 32 + frow;
+            const float sx = sxr[i];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int nt = wn * G::WTN + j * 32 + 8 * q + 4 * fhalf;
+                float y[4];
+                const float snv[4] = {sn[q].x, sn[q].y, sn[q].z, sn[q].w}, bsv[4] = {bs[q].x, bs[q].y, bs[q].z, bs[q].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = 4 * q + e;
+                    float v;
+                    if constexpr (HASO) {
+                        const float sov[4] = {so[q].x, so[q].y, so[q].z, so[q].w};
+                        v = (float)ao[r] * sov[e];
+                        v = fmaf((float)acc[i][j][r], snv[e], v);
+                    } else {
+                        // acc_o == 0: (float)0 * s_o is +0 and the first fma reduces to this one
+                        v = fmaf((float)acc[i][j][r], snv[e], 0.0f);
                     }
+                    y[e] = fmaf(v, sx, bsv[e]);
                 }
+                if constexpr (DBG) {
+                    const int n = n0 + nt;
+                    if (m_lane < g.M && n + 4 <= g.N) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int nl = j * 32 + 8 * q + 4 * fhalf;            // column inside the wave tile
-                    const int nt = wn * G::WTN + nl;                       // column inside the workgroup tile
-                    const v4f sn = *reinterpret_cast<const v4f *>(sn_lds + nt);
-                    const v4f so = *reinterpret_cast<const v4f *>(so_lds + nt);
-                    const v4f bs = *reinterpret_cast<const v4f *>(bs_lds + nt);
-                    float y[4];
-                    const float snv[4] = {sn.x, sn.y, sn.z, sn.w}, sov[4] = {so.x, so.y, so.z, so.w};
-                    const float bsv[4] = {bs.x, bs.y, bs.z, bs.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int r = 4 * q + e;
-                        float v;
-                        if constexpr (HASO) {
-                            v = (float)ao[r] * sov[e];
-                            v = fmaf((float)acc[i][j][r], snv[e], v);
-                        } else {
-                            // acc_o == 0: (float)0 * s_o is +0 and the first fma reduces to this one
-                            v = fmaf((float)acc[i][j][r], snv[e], 0.0f);
-                        }
-                        y[e] = fmaf(v, sx, bsv[e]);
-                    }
-                    if constexpr (DBG) {
-                        const int n = n0 + nt;
-                        if (m_lane < g.M && n + 4 <= g.N) {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                // (INT4 codes were multiplied by 16 on the way in: the sums are exact multiples)
-                                if (g.dbg_n) g.dbg_n[(size_t)m_lane * g.N + n + e] = acc[i][j][4 * q + e] >> (W4 ? 4 : 0);
-                                if (g.dbg_o) g.dbg_o[(size_t)m_lane * g.N + n + e] = HASO ? ao[4 * q + e] >> (W4 ? 4 : 0) : 0;
+                        for (int e = 0; e < 4; ++e) {
+                            // (INT4 codes were multiplied by 16 on the way in: the sums are exact multiples)
+                            if (g.dbg_n) g.dbg_n[(size_t)m_lane * g.N + n + e] = acc[i][j][4 * q + e] >> (W4 ? 4 : 0);
+                            if (g.dbg_o) {
+                                int aov = 0;
+                                if constexpr (HASO) aov = ao[4 * q + e] >> (W4 ? 4 : 0);
+                                g.dbg_o[(size_t)m_lane * g.N + n + e] = aov;
                             }
                         }
                     }
-                    if (i == 0 && j == 0 && q == 0) {
-                        // The next tile's first stages were issued when this epilogue began and have had its
-                        // first block's arithmetic to land.  Waiting for them here, before the first output
-                        // store is issued, means no later wait for a stage load ever has an output store ahead
-                        // of it in the (in-order) memory counter.
-                        __builtin_amdgcn_sched_barrier(0);
-                        wait_vmcnt<0>();
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    if constexpr (sizeof(OutT) == 1) {
-                        // chained layer: activation, then the next layer's static scale (Eq. (quantization)); two
-                        // blocks of 32 INT8 columns share a 64-byte patch row
-                        static_assert(sizeof(OutT) != 1 || TN % 2 == 0, "INT8 output pairs the column blocks");
-                        const unsigned pk = quantize4_static(y, g.act == 1, g.out_scale, out_rscale);
-                        const int c = 2 * (j & 1) + (q >> 1);
-                        *reinterpret_cast<unsigned *>(patch + frow * PATCH_RS + ((c ^ pswz) << 4) + 8 * (q & 1) + 4 * fhalf) = pk;
-                    } else if constexpr (sizeof(OutT) == 2) {
-                        v2u pk;
-                        pk.x = cvt_pk_bf16(y[0], y[1]);
-                        pk.y = cvt_pk_bf16(y[2], y[3]);
-                        *reinterpret_cast<v2u *>(patch + frow * PATCH_RS + ((q ^ pswz) << 4) + 8 * fhalf) = pk;
-                    } else {
-                        const int c = 2 * (q & 1) + fhalf;
-                        *reinterpret_cast<v4f *>(patch + frow * PATCH_RS + ((c ^ pswz) << 4)) = v4f{y[0], y[1], y[2], y[3]};
-                        if (q & 1) flush_patch(i, j * 32 + (q >> 1) * 16);
-                    }
+                }
+                if constexpr (sizeof(OutT) == 1) {
+                    // chained layer: activation, then the next layer's static scale (Eq. (quantization)); two
+                    // blocks of 32 INT8 columns share a 64-byte patch row
+                    static_assert(sizeof(OutT) != 1 || TN % 2 == 0, "INT8 output pairs the column blocks");
+                    const unsigned pk = quantize4_static(y, g.act == 1, g.out_scale, out_rscale);
+                    const int c = 2 * (j & 1) + (q >> 1);
+                    *reinterpret_cast<unsigned *>(patch + frow * PATCH_RS + ((c ^ pswz) << 4) + 8 * (q & 1) + 4 * fhalf) = pk;
+                } else if constexpr (sizeof(OutT) == 2) {
+                    v2u pk;
+                    pk.x = cvt_pk_bf16(y[0], y[1]);
+                    pk.y = cvt_pk_bf16(y[2], y[3]);
+                    *reinterpret_cast<v2u *>(patch + frow * PATCH_RS + ((q ^ pswz) << 4) + 8 * fhalf) = pk;
+                } else {
+                    const int c = 2 * (q & 1) + fhalf;
+                    *reinterpret_cast<v4f *>(patch + frow * PATCH_RS + ((c ^ pswz) << 4)) = v4f{y[0], y[1], y[2], y[3]};
+                    if (q & 1) flush(i, j * 32 + (q >> 1) * 16);
                 }
             }
-            if constexpr (sizeof(OutT) == 2) flush_patch(i, j * 32);
+            if constexpr (sizeof(OutT) == 2) flush(i, j * 32);
             if constexpr (sizeof(OutT) == 1) {
-                if (j & 1) flush_patch(i, (j - 1) * 32);
+                if (j & 1) flush(i, (j - 1) * 32);
             }
         }
-    }
+        flush_commit();
     };
     if constexpr (DUAL) {
         if (has_o) epilogue(std::true_type{});
@@ -513,7 +557,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
         OutT *Yp = reinterpret_cast<OutT *>(g.Y);
         int *o = (DBG && g.dbg_o) ? g.dbg_o + ((size_t)blockIdx.x * NW + wave) * 8
                                   : reinterpret_cast<int *>(Yp + (size_t)g.M * g.ldy) + ((size_t)blockIdx.x * NW + wave) * 8;
-        o[0] = (int)p_loop; o[1] = (int)p_vm; o[2] = (int)p_bar; o[3] = (int)p_epi; o[4] = (int)(wall_clock64() - p_rs);
+        o[0] = (int)p_loop; o[1] = (int)(QARVD_PROF == 2 ? p_vmw : p_vm); o[2] = (int)p_bar; o[3] = (int)p_epi; o[4] = (int)(wall_clock64() - p_rs);
         o[5] = p_tiles; o[6] = (int)(clock64() - p_ts); o[7] = (int)p_pro;
     }
 #endif
