@@ -78,38 +78,72 @@ __global__ __launch_bounds__(NT) void quant_act_rows_kernel(ActArgs a)
     const int tid = threadIdx.x;
     const int K = a.K, kp = a.kp;
 
+    const T *X = reinterpret_cast<const T *>(a.X);
+    auto load_row = [&](int m, float4 (&v)[CH]) {
+        const T *x = X + (size_t)m * a.ldx;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int k = 4 * (tid + c * NT);
+            if (k < K) v[c] = Vec4Loader<T>::load(x + k);
+        }
+    };
+    float4 v[CH], vn[CH];
+    int m = blockIdx.x;
+
     if constexpr (!IDENT) {
         // channel -> packed position (a perm that is not a bijection gives undefined bytes, never an
-        // out-of-range LDS access: every entry starts at a valid position and bad indices are skipped)
-        if (a.perm) {
-            for (int k = tid; k < K; k += NT) pos[k] = (PosT)a.n_off;
-            __syncthreads();
-            for (int p = tid; p < K; p += NT) {
-                const int k = a.perm[p];
-                if ((unsigned)k < (unsigned)K) pos[k] = (PosT)(p < a.K_o ? p : a.n_off + (p - a.K_o));
+        // out-of-range LDS access: every entry starts at a valid position and bad indices are skipped).
+        // perm is fetched first, four entries per lane, then the first row: both are in flight while the
+        // table and the row images are initialised, and the table is complete before the row lands.
+        const bool pvec = a.perm && (reinterpret_cast<uintptr_t>(a.perm) & 15) == 0;
+        int4 pv[CH];
+        if (pvec) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int i4 = tid + c * NT;
+                if (4 * i4 < K) pv[c] = reinterpret_cast<const int4 *>(a.perm)[i4];
             }
-        } else {
-            for (int k = tid; k < K; k += NT) pos[k] = (PosT)k;
         }
+        if (m < a.M) load_row(m, v);
+        for (int k = tid; k < K; k += NT) pos[k] = (PosT)(a.perm ? a.n_off : k);
         // zero both row images once: padding bytes are never overwritten afterwards
         for (int i = tid; i < (2 * kp) / 16; i += NT) reinterpret_cast<uint4 *>(qbuf)[i] = make_uint4(0, 0, 0, 0);
         __syncthreads();
+        if (a.perm) {
+            auto place = [&](int p, int k) {
+                if ((unsigned)k < (unsigned)K) pos[k] = (PosT)(p < a.K_o ? p : a.n_off + (p - a.K_o));
+            };
+            if (pvec) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const int p = 4 * (tid + c * NT);
+                    if (p < K) {
+                        place(p, pv[c].x);
+                        place(p + 1, pv[c].y);
+                        place(p + 2, pv[c].z);
+                        place(p + 3, pv[c].w);
+                    }
+                }
+            } else {
+                for (int p = tid; p < K; p += NT) place(p, a.perm[p]);
+            }
+            __syncthreads();
+        }
+    } else {
+        if (m < a.M) load_row(m, v);
     }
 
-    const T *X = reinterpret_cast<const T *>(a.X);
     int buf = 0;
-    for (int m = blockIdx.x; m < a.M; m += gridDim.x, buf ^= 1) {
-        const T *x = X + (size_t)m * a.ldx;
-        float4 v[CH];
+    for (; m < a.M; m += gridDim.x, buf ^= 1) {
         float amax = 0.0f;
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
             const int k = 4 * (tid + c * NT);
-            if (k < K) {
-                v[c] = Vec4Loader<T>::load(x + k);
-                amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[c].x), fabsf(v[c].y)), fmaxf(fabsf(v[c].z), fabsf(v[c].w))));
-            }
+            if (k < K) amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[c].x), fabsf(v[c].y)), fmaxf(fabsf(v[c].z), fabsf(v[c].w))));
         }
+        // the next row's loads fly under this row's reduction, quantization and copy-out
+        const bool more = m + (int)gridDim.x < a.M;
+        if (more) load_row(m + gridDim.x, vn);
         float s;
         if (STATIC) {
             s = a.static_scale;
@@ -150,6 +184,10 @@ __global__ __launch_bounds__(NT) void quant_act_rows_kernel(ActArgs a)
             for (int i = tid; i < kp / 16; i += NT)
                 reinterpret_cast<uint4 *>(out)[i] = reinterpret_cast<const uint4 *>(q)[i];
         }
+        if (more) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) v[c] = vn[c];
+        }
     }
 }
 
@@ -168,8 +206,18 @@ __global__ __launch_bounds__(TPB) void quant_act_wave_kernel(ActArgs a)
     const T *X = reinterpret_cast<const T *>(a.X);
     const int wave_id = blockIdx.x * 4 + wave, n_waves = gridDim.x * 4;
 
-    // the first row's loads go out before the position table is built: their memory latency and the
-    // table's (perm is read from cache) overlap
+    // perm is fetched first (four entries per lane), then the first row: both are in flight while the table
+    // and the images are initialised, and the table is complete before the row lands
+    constexpr int PCH = (CH + 3) / 4;
+    const bool pvec = a.perm && (reinterpret_cast<uintptr_t>(a.perm) & 15) == 0;
+    int4 pv[PCH];
+    if (pvec) {
+#pragma unroll
+        for (int c = 0; c < PCH; ++c) {
+            const int i4 = tid + c * TPB;
+            if (4 * i4 < K) pv[c] = reinterpret_cast<const int4 *>(a.perm)[i4];
+        }
+    }
     float4 v[CH];
     auto load_row = [&](int m) {
         const T *x = X + (size_t)m * a.ldx;
@@ -182,18 +230,29 @@ __global__ __launch_bounds__(TPB) void quant_act_wave_kernel(ActArgs a)
     int m = wave_id;
     if (m < a.M) load_row(m);
 
-    if (a.perm) {
-        for (int k = tid; k < K; k += TPB) pos[k] = (uint16_t)a.n_off;
-        __syncthreads();
-        for (int p = tid; p < K; p += TPB) {
-            const int k = a.perm[p];
-            if ((unsigned)k < (unsigned)K) pos[k] = (uint16_t)(p < a.K_o ? p : a.n_off + (p - a.K_o));
-        }
-    } else {
-        for (int k = tid; k < K; k += TPB) pos[k] = (uint16_t)k;
-    }
+    for (int k = tid; k < K; k += TPB) pos[k] = (uint16_t)(a.perm ? a.n_off : k);
     for (int i = tid; i < (4 * kp) / 16; i += TPB) reinterpret_cast<uint4 *>(smem)[i] = make_uint4(0, 0, 0, 0);
     __syncthreads();
+    if (a.perm) {
+        auto place = [&](int p, int k) {
+            if ((unsigned)k < (unsigned)K) pos[k] = (uint16_t)(p < a.K_o ? p : a.n_off + (p - a.K_o));
+        };
+        if (pvec) {
+#pragma unroll
+            for (int c = 0; c < PCH; ++c) {
+                const int p = 4 * (tid + c * TPB);
+                if (p < K) {
+                    place(p, pv[c].x);
+                    place(p + 1, pv[c].y);
+                    place(p + 2, pv[c].z);
+                    place(p + 3, pv[c].w);
+                }
+            }
+        } else {
+            for (int p = tid; p < K; p += TPB) place(p, a.perm[p]);
+        }
+        __syncthreads();
+    }
 
     for (; m < a.M; m += n_waves) {
         float amax = 0.0f;
