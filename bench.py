@@ -310,6 +310,47 @@ def main():
             del w1, w1u, w2, X, Xq1, H8, Hb, Yf
         except Exception as e:  # diagnostic only
             out["chained_ffn"] = dict(error=str(e))
+    if tgt and args.config == 2:   # q, k, v of one block as ONE layer (rows concatenated, one shared outlier set)
+        try:
+            names = ["cfg2.q.c16", "cfg2.k.c16", "cfg2.v.c16"]
+            parts = [l for l in layers if l["spec"].name in names]
+            Ws = [torch.from_numpy(wl.make_layer(l["spec"])["W"]).to(dev) for l in parts]
+            wf = q.quantize_weight(torch.cat(Ws, 0), want_norms=False)
+            bf = torch.cat([l["bias"] for l in parts])
+            del Ws
+            X0, M0 = parts[0]["X"], parts[0]["spec"].M
+            Xqf = torch.empty((M0, wf.kp), dtype=torch.int8, device=dev)
+            sxf = torch.empty(M0, dtype=torch.float32, device=dev)
+            Yf3 = torch.empty((M0, wf.N), dtype=torch.bfloat16, device=dev)
+
+            def fused():
+                q.quant_act(X0, wf.perm if wf.K_o else None, wf.K_o, Xq=Xqf, s_x=sxf)
+                q.w8a8_dual_gemm(Xqf, sxf, wf, bf, M0, Y=Yf3)
+
+            def three():
+                for l in parts:
+                    run_quant(l)
+                    run_gemm(l)
+
+            def time_us3(fn):
+                for _ in range(5):
+                    fn()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(args.steps):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                return 1e3 * e0.elapsed_time(e1) / args.steps
+
+            us_f, us_3 = time_us3(fused), time_us3(three)
+            out["fused_qkv"] = dict(shape="M=4680, 1536 -> 3 x 1536 as one N=4608 layer", K_o=wf.K_o,
+                                    fused_us=round(us_f, 1), separate_us=round(us_3, 1), speedup=round(us_3 / us_f, 3),
+                                    note="one quant_act + one dual GEMM over the concatenated rows against three "
+                                         "quant_act + GEMM pairs (which also read three different activations)")
+            del wf, Xqf, Yf3
+        except Exception as e:  # diagnostic only
+            out["fused_qkv"] = dict(error=str(e))
     out["paper_context"] = "paper reports 1.30x end-to-end INT8 speedup and 1.97x size reduction on an NVIDIA A6000 " \
                            "with Triton kernels (whole pipeline, not this kernel)"
 

@@ -118,9 +118,38 @@ def quantize_rows(W, perm, K_o):
     return Wq, sn, so
 
 
-def quantize_weight(W, tau=3.5, alpha=1.2, align=32, forced_mask=None, bits=8):
+def clip_search(w, qmax=127.0):
+    """Percentile-clip scale of one block (Sec. 4.1): returns dict(s, choice, clip[3], sse[3])."""
+    w = np.ascontiguousarray(w, dtype=np.float32).ravel()
+    s = C.c_float(0.0)
+    ch = C.c_int(0)
+    clip = np.zeros(3, np.float32)
+    sse = np.zeros(3, np.float64)
+    _check(_load().oracle_clip_search(_p(w, C.c_float), int(w.size), C.c_float(qmax), C.byref(s), C.byref(ch),
+                                      _p(clip, C.c_float), _p(sse, C.c_double)))
+    return dict(s=np.float32(s.value), choice=int(ch.value), clip=clip, sse=sse)
+
+
+def quantize_rows_clip(W, perm, K_o, bits=8):
+    """quantize_rows with percentile-clip scales.  Returns (Wq, s_normal, s_outlier, choice_n, choice_o)."""
+    W = _f32(W)
+    N, K = W.shape
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    Wq = np.empty((N, K), np.int8)
+    sn = np.empty(N, np.float32)
+    so = np.empty(N, np.float32)
+    cn = np.empty(N, np.int8)
+    co = np.empty(N, np.int8)
+    _check(_load().oracle_quantize_rows_clip(_p(W, C.c_float), N, K, _p(perm, C.c_int32), int(K_o), int(bits),
+                                             _p(Wq, C.c_int8), _p(sn, C.c_float), _p(so, C.c_float),
+                                             _p(cn, C.c_int8), _p(co, C.c_int8)))
+    return Wq, sn, so, cn, co
+
+
+def quantize_weight(W, tau=3.5, alpha=1.2, align=32, forced_mask=None, bits=8, clip_search=False):
     """Returns dict(Wq, s_normal, s_outlier, perm, K_o, v, flag, stats).  bits=4: codes in [-7, 7]
-    (one per int8 element), scales = block absmax / 7 (the W4A8 setting of Sec. 4.2)."""
+    (one per int8 element), scales = block absmax / 7 (the W4A8 setting of Sec. 4.2).  clip_search:
+    scales from the percentile-clip search of Sec. 4.1 instead of the block absmax."""
     W = _f32(W)
     N, K = W.shape
     Wq = np.empty((N, K), np.int8)
@@ -132,9 +161,9 @@ def quantize_weight(W, tau=3.5, alpha=1.2, align=32, forced_mask=None, bits=8):
     st = np.zeros(4, np.float64)
     ko = C.c_int32(0)
     fm = None if forced_mask is None else np.ascontiguousarray(forced_mask, dtype=np.uint8)
-    _check(_load().oracle_quantize_weight_bits(
+    _check(_load().oracle_quantize_weight_clip(
         _p(W, C.c_float), N, K, C.c_double(tau), C.c_double(alpha), int(align), _p(fm, C.c_uint8), int(bits),
-        _p(Wq, C.c_int8), _p(sn, C.c_float), _p(so, C.c_float), _p(perm, C.c_int32), C.byref(ko),
+        int(bool(clip_search)), _p(Wq, C.c_int8), _p(sn, C.c_float), _p(so, C.c_float), _p(perm, C.c_int32), C.byref(ko),
         _p(v, C.c_float), _p(flag, C.c_uint8), _p(st, C.c_double)))
     return dict(Wq=Wq, s_normal=sn, s_outlier=so, perm=perm, K_o=int(ko.value), v=v, flag=flag,
                 stats=dict(med=st[0], mad=st[1], T=st[2], n_det=int(st[3])))

@@ -258,6 +258,118 @@ int oracle_quantize_rows_bits(const float *W, int N, int K, const int32_t *perm,
     return ORACLE_OK;
 }
 
+/* ---------------- percentile-clip initialisation of the weight scales (Sec. 4.1) */
+
+static int cmp_float_asc(const void *a, const void *b)
+{
+    float x = *(const float *)a, y = *(const float *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * Sec. 4.1 "Quantization Implementation": the scaling factors are initialised by searching the clipping
+ * percentile over {0.999, 0.9999, 0.99999}.  The paper states neither the objective nor the percentile
+ * convention; the reading taken (data-free, for one block of one output row, n values w[0..n-1]):
+ *   a = |w| sorted ascending;  for p in the list:  h = (n-1) p,  lo = floor(h),
+ *       clip_p = a[lo] + (h - lo) (a[min(lo+1, n-1)] - a[lo])      (linear interpolation, in double, rounded to float)
+ *       s_p = clip_p / qmax,  q_i = clip(rint(w_i / s_p), -qmax, qmax),
+ *       e_i = fmaf(-s_p, q_i, w_i) (float),  SSE_p = sum_i (double)e_i^2, i ascending, in double;
+ *   the percentile with the smallest SSE wins, the LARGER percentile on a tie (least clipping).
+ * Outputs: *s_out the chosen scale, *choice_out 0/1/2 = index into the list; clip_out[3], sse_out[3]
+ * (nullable) the candidates.  n == 0: scale 0, choice 2.
+ */
+int oracle_clip_search(const float *w, int n, float qmax, float *s_out, int *choice_out,
+                       float *clip_out, double *sse_out)
+{
+    static const double P[3] = {0.999, 0.9999, 0.99999};
+    float *a, clip[3], s[3];
+    double sse[3];
+    int best;
+    if (!w || n < 0 || !s_out || !choice_out || !(qmax >= 1.0f))
+        return ORACLE_BAD_ARG;
+    if (n == 0) {
+        *s_out = 0.0f;
+        *choice_out = 2;
+        return ORACLE_OK;
+    }
+    a = (float *)malloc((size_t)n * sizeof(float));
+    for (int i = 0; i < n; ++i)
+        a[i] = fabsf(w[i]);
+    qsort(a, (size_t)n, sizeof(float), cmp_float_asc);
+    for (int c = 0; c < 3; ++c) {
+        double h = (double)(n - 1) * P[c];
+        int lo = (int)floor(h);
+        int hi = lo + 1 < n ? lo + 1 : n - 1;
+        double frac = h - (double)lo;
+        clip[c] = (float)((double)a[lo] + frac * ((double)a[hi] - (double)a[lo]));
+        s[c] = clip[c] / qmax;
+        sse[c] = 0.0;
+        for (int i = 0; i < n; ++i) {
+            float q = (float)quantize_sym(w[i], s[c], qmax);
+            float e = fmaf(-s[c], q, w[i]);
+            sse[c] += (double)e * (double)e;
+        }
+    }
+    free(a);
+    best = 2;
+    for (int c = 1; c >= 0; --c)
+        if (sse[c] < sse[best])
+            best = c;
+    *s_out = s[best];
+    *choice_out = best;
+    for (int c = 0; c < 3; ++c) {
+        if (clip_out)
+            clip_out[c] = clip[c];
+        if (sse_out)
+            sse_out[c] = sse[c];
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * oracle_quantize_rows_bits with the two scales of every row chosen by oracle_clip_search over the
+ * row's outlier block and normal block (values taken in packed order) instead of block absmax / qmax.
+ * choice_n / choice_o (nullable, [N]): the winning percentile index of each block.
+ */
+int oracle_quantize_rows_clip(const float *W, int N, int K, const int32_t *perm, int K_o, int bits,
+                              int8_t *Wq, float *s_normal, float *s_outlier, int8_t *choice_n,
+                              int8_t *choice_o)
+{
+    float qmax;
+    int bad = 0;
+    if (!W || !perm || !Wq || !s_normal || !s_outlier || N <= 0 || K <= 0 || K_o < 0 || K_o > K ||
+        (bits != 8 && bits != 4))
+        return ORACLE_BAD_ARG;
+    qmax = bits == 8 ? 127.0f : 7.0f;
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < N; ++j) {
+        const float *w = W + (size_t)j * K;
+        float *blk = (float *)malloc((size_t)K * sizeof(float));
+        float so, sn;
+        int co, cn;
+        for (int p = 0; p < K; ++p)
+            blk[p] = w[perm[p]];
+        if (oracle_clip_search(blk, K_o, qmax, &so, &co, NULL, NULL) != ORACLE_OK ||
+            oracle_clip_search(blk + K_o, K - K_o, qmax, &sn, &cn, NULL, NULL) != ORACLE_OK) {
+#pragma omp atomic write
+            bad = 1;
+        } else {
+            s_outlier[j] = so;
+            s_normal[j] = sn;
+            if (choice_o)
+                choice_o[j] = (int8_t)co;
+            if (choice_n)
+                choice_n[j] = (int8_t)cn;
+            for (int p = 0; p < K_o; ++p)
+                Wq[(size_t)j * K + p] = quantize_sym(blk[p], so, qmax);
+            for (int p = K_o; p < K; ++p)
+                Wq[(size_t)j * K + p] = quantize_sym(blk[p], sn, qmax);
+        }
+        free(blk);
+    }
+    return bad ? ORACLE_BAD_ARG : ORACLE_OK;
+}
+
 int oracle_quantize_rows(const float *W, int N, int K, const int32_t *perm, int K_o,
                          int8_t *Wq, float *s_normal, float *s_outlier)
 {
@@ -270,10 +382,10 @@ int oracle_quantize_rows(const float *W, int N, int K, const int32_t *perm, int 
  * detection and alignment.  Optional outputs (nullable): v_out[K], flag_out[K]
  * (raw detector flags before alignment), stats[4].
  */
-int oracle_quantize_weight_bits(const float *W, int N, int K, double tau, double alpha, int align,
-                                const uint8_t *forced_mask, int bits, int8_t *Wq, float *s_normal,
-                                float *s_outlier, int32_t *perm, int32_t *K_o_out, float *v_out,
-                                uint8_t *flag_out, double *stats)
+int oracle_quantize_weight_clip(const float *W, int N, int K, double tau, double alpha, int align,
+                                const uint8_t *forced_mask, int bits, int clip_search, int8_t *Wq,
+                                float *s_normal, float *s_outlier, int32_t *perm, int32_t *K_o_out,
+                                float *v_out, uint8_t *flag_out, double *stats)
 {
     float *v;
     uint8_t *sel;
@@ -300,7 +412,8 @@ int oracle_quantize_weight_bits(const float *W, int N, int K, double tau, double
     if (rc == ORACLE_OK)
         rc = oracle_build_perm(sel, K, perm, &K_o);
     if (rc == ORACLE_OK)
-        rc = oracle_quantize_rows_bits(W, N, K, perm, K_o, bits, Wq, s_normal, s_outlier);
+        rc = clip_search ? oracle_quantize_rows_clip(W, N, K, perm, K_o, bits, Wq, s_normal, s_outlier, NULL, NULL)
+                         : oracle_quantize_rows_bits(W, N, K, perm, K_o, bits, Wq, s_normal, s_outlier);
     if (rc == ORACLE_OK) {
         *K_o_out = K_o;
         if (v_out)
@@ -309,6 +422,15 @@ int oracle_quantize_weight_bits(const float *W, int N, int K, double tau, double
     free(v);
     free(sel);
     return rc;
+}
+
+int oracle_quantize_weight_bits(const float *W, int N, int K, double tau, double alpha, int align,
+                                const uint8_t *forced_mask, int bits, int8_t *Wq, float *s_normal,
+                                float *s_outlier, int32_t *perm, int32_t *K_o_out, float *v_out,
+                                uint8_t *flag_out, double *stats)
+{
+    return oracle_quantize_weight_clip(W, N, K, tau, alpha, align, forced_mask, bits, 0, Wq, s_normal,
+                                       s_outlier, perm, K_o_out, v_out, flag_out, stats);
 }
 
 int oracle_quantize_weight(const float *W, int N, int K, double tau, double alpha, int align,

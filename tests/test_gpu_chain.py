@@ -214,3 +214,28 @@ def test_chained_ffn_full_size_sampled_rows():
     Y = q.w8a8_dual_gemm(H8, s_rows, w2, dev(b2), up.M, torch.bfloat16)
     torch.cuda.synchronize()
     assert bf16_ulp_distance(bf16_bits(Y[rt]), out["Y_bf16"]).max() <= 1
+
+
+def test_fused_qkv_as_one_layer_sampled_rows():
+    """Three projections of one block as ONE layer (weight rows concatenated, N = 4608, one shared outlier
+    set from the concatenated matrix): the ordinary entry points on a wider N; sampled rows against the oracle."""
+    specs = [wl.find_layer(n) for n in ("cfg2.q.c16", "cfg2.k.c16", "cfg2.v.c16")]
+    Ls = [wl.make_layer(s) for s in specs]
+    W = np.concatenate([L["W"] for L in Ls], 0)
+    b = np.concatenate([L["bias"] for L in Ls])
+    X = Ls[0]["X"]
+    M = specs[0].M
+    o = oracle.quantize_weight(W)
+    w = gpu_quantize_weight(W)
+    assert w.K_o == o["K_o"] and w.N == 4608 and np.array_equal(w.perm.cpu().numpy(), o["perm"])
+    rng = np.random.default_rng(77)
+    rows = np.unique(np.concatenate([[0, M - 1], rng.choice(M, 30, replace=False)]))
+    Xq_o, sx_o = oracle.quant_act(X[rows], o["perm"])
+    ref = oracle.dual_gemm(Xq_o, sx_o, o["Wq"], o["s_normal"], o["s_outlier"], b, o["K_o"])
+    Xq, sx = q.quant_act(dev(X), w.perm if w.K_o else None, w.K_o)
+    Y = q.w8a8_dual_gemm(Xq, sx, w, dev(b), M, torch.bfloat16)
+    torch.cuda.synchronize()
+    rt = torch.from_numpy(rows).cuda()
+    assert np.array_equal(logical(Xq[rt], w.K, w.K_o), Xq_o)
+    assert np.array_equal(sx[rt].cpu().numpy().view(np.uint32), sx_o.view(np.uint32))
+    assert bf16_ulp_distance(bf16_bits(Y[rt]), ref["Y_bf16"]).max() <= 1
