@@ -57,6 +57,13 @@ typedef enum { QARVD_F32 = 0, QARVD_BF16 = 1 } qarvd_dtype;
 /*
  * Detector parameters (Sec. 3.2, Eq. (new_threshold): tau = 3.5, alpha = 1.2; Fig. "outlier
  * patterns" caption: the outlier count is aligned to a multiple of 32).
+ *   clip_search  0: each scale is the block's absmax / qmax (Eq. (quantization)).  1: percentile-clip
+ *                initialisation (Sec. 4.1 "Quantization Implementation": the clipping percentile is
+ *                searched over {0.999, 0.9999, 0.99999}), data-free, per output row and block: the
+ *                linear-interpolated p-quantile of |w| (h = (n-1) p, in double, rounded to float) over
+ *                qmax is a candidate scale; the one with the smallest squared quantization error
+ *                sum (fmaf(-s, q, w))^2 (summed in double in packed order) wins, the larger percentile
+ *                on a tie.  Needs K <= 16384.
  *   forced_mask  HOST pointer to K bytes (0/1) or NULL.  Non-NULL: the outlier set is exactly
  *                the mask; detection and alignment are skipped (used for the all-outlier and
  *                arbitrary-split checks).
@@ -65,10 +72,11 @@ typedef struct {
     double tau;
     double alpha;
     int32_t align;
+    int32_t clip_search;
     const uint8_t *forced_mask;
 } qarvd_detect_cfg;
 
-/* Fills *cfg with the paper's defaults {3.5, 1.2, 32, NULL}. */
+/* Fills *cfg with the paper's defaults {3.5, 1.2, 32, 0, NULL}. */
 void qarvd_default_detect_cfg(qarvd_detect_cfg *cfg);
 
 /* Human-readable name of a status code (static storage). */

@@ -28,7 +28,7 @@ class QarvdError(RuntimeError):
 
 
 class _DetectCfg(C.Structure):
-    _fields_ = [("tau", C.c_double), ("alpha", C.c_double), ("align", C.c_int32),
+    _fields_ = [("tau", C.c_double), ("alpha", C.c_double), ("align", C.c_int32), ("clip_search", C.c_int32),
                 ("forced_mask", C.c_void_p)]
 
 
@@ -188,9 +188,10 @@ class DualScaleWeight:
 
 def quantize_weight(W: torch.Tensor, tau: float = 3.5, alpha: float = 1.2, align: int = 32,
                     forced_mask=None, ldwq: Optional[int] = None, want_norms: bool = True,
-                    stream=None, bits: int = 8) -> DualScaleWeight:
+                    stream=None, bits: int = 8, clip_search: bool = False) -> DualScaleWeight:
     """qarvd_quantize_weight (bits=8) / qarvd_quantize_weight_w4 (bits=4): W f32 [N,K] on the device ->
-    packed dual-scale layer.  For bits=4 `ldwq` is in bytes (two codes per byte)."""
+    packed dual-scale layer.  For bits=4 `ldwq` is in bytes (two codes per byte).  clip_search: scales from
+    the percentile-clip search instead of the block absmax."""
     lib = load_library()
     _dev2d(W, "W")
     if W.dtype != torch.float32:
@@ -211,7 +212,7 @@ def quantize_weight(W: torch.Tensor, tau: float = 3.5, alpha: float = 1.2, align
     ws_bytes = quantize_weight_workspace(N, K) if bits == 8 else int(lib.qarvd_quantize_weight_w4_workspace(N, K))
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
     ws_ptr = (ws.data_ptr() + 255) // 256 * 256
-    cfg = _DetectCfg(float(tau), float(alpha), int(align), None)
+    cfg = _DetectCfg(float(tau), float(alpha), int(align), int(bool(clip_search)), None)
     keep = None
     if forced_mask is not None:
         import numpy as np

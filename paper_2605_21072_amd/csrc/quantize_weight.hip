@@ -168,6 +168,83 @@ __global__ __launch_bounds__(1024) void build_perm_kernel(const uint8_t *__restr
 }
 
 // ---- dual scales + INT8 rows -------------------------------------------------------------
+// Percentile-clip initialisation of the two scales of every output row (Sec. 4.1 "Quantization
+// Implementation": the clipping percentile is searched over {0.999, 0.9999, 0.99999}).  Per row and block,
+// with the block's n values taken in packed order:
+//     clip_p = linear-interpolated p-quantile of |w|  (h = (n-1) p, a[floor h] + frac (a[floor h + 1] - a[floor h]),
+//              in double, rounded to float),  s_p = clip_p / qmax,
+//     SSE_p  = sum (double) e^2,  e = fmaf(-s_p, q(w, s_p), w),  summed in packed order in double;
+//     the smallest SSE wins, the larger percentile on a tie.
+// The sums are order-dependent in their last bits and decide an integer, so one thread owns one block of one
+// row and walks it serially (this is the offline step).  Only the CLIP_TOP largest magnitudes are ever needed:
+// n - 1 - floor(0.999 (n-1)) < CLIP_TOP for n <= 16384.
+constexpr int CLIP_TOP = 20;
+__global__ __launch_bounds__(64) void clip_search_kernel(const float *__restrict__ W, int N, int K, int64_t ldw,
+                                                         const int32_t *__restrict__ perm, const DetectScalars *sc,
+                                                         float qmax, float *__restrict__ s_normal,
+                                                         float *__restrict__ s_outlier)
+{
+    const int t = blockIdx.x * 64 + threadIdx.x;
+    if (t >= 2 * N) return;
+    const int blk = t / N, j = t - blk * N;            // the first N threads take the outlier blocks
+    const int K_o = sc->K_o;
+    const int p0 = blk ? K_o : 0, n = blk ? K - K_o : K_o;
+    float *dst = blk ? s_normal : s_outlier;
+    if (n == 0) {
+        dst[j] = 0.0f;
+        return;
+    }
+    const float *w = W + (size_t)j * ldw;
+    float top[CLIP_TOP];                               // ascending; -1 marks an empty slot (magnitudes are >= 0)
+#pragma unroll
+    for (int i = 0; i < CLIP_TOP; ++i) top[i] = -1.0f;
+    for (int p = p0; p < p0 + n; ++p) {
+        const float a = fabsf(w[perm[p]]);
+        if (a > top[0]) {
+            top[0] = a;
+#pragma unroll
+            for (int i = 0; i + 1 < CLIP_TOP; ++i) {
+                const float lo = fminf(top[i], top[i + 1]), hi = fmaxf(top[i], top[i + 1]);
+                top[i] = lo;
+                top[i + 1] = hi;
+            }
+        }
+    }
+    auto order_stat = [&](int i) {                     // a_(i) of the ascending order, i >= n - CLIP_TOP
+        const int slot = CLIP_TOP - n + i;
+        float r = top[0];
+#pragma unroll
+        for (int u = 1; u < CLIP_TOP; ++u) r = u == slot ? top[u] : r;
+        return r;
+    };
+    const double P[3] = {0.999, 0.9999, 0.99999};
+    float s[3];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+        const double h = (double)(n - 1) * P[c];
+        const int lo = (int)floor(h);
+        const int hi = lo + 1 < n ? lo + 1 : n - 1;
+        const double frac = h - (double)lo;
+        const double alo = (double)order_stat(lo), ahi = (double)order_stat(hi);
+        const float clip = (float)(alo + frac * (ahi - alo));
+        s[c] = clip / qmax;
+    }
+    double sse[3] = {0.0, 0.0, 0.0};
+    for (int p = p0; p < p0 + n; ++p) {
+        const float x = w[perm[p]];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const float q = (float)quantize_sym(x, s[c], qmax);
+            const float e = fmaf(-s[c], q, x);
+            sse[c] += (double)e * (double)e;
+        }
+    }
+    int best = 2;
+    if (sse[1] < sse[best]) best = 1;
+    if (sse[0] < sse[best]) best = 0;
+    dst[j] = best == 2 ? s[2] : best == 1 ? s[1] : s[0];
+}
+
 // One workgroup per output row.  Pass 1: absmax of each block; pass 2: quantize and store each
 // byte at its packed position (the row is re-read from cache).  K_o is read from the workspace
 // scalars so that no host round trip sits between detection and quantization.
@@ -175,7 +252,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const float *__restr
                                                             const int32_t *__restrict__ pos, const DetectScalars *sc,
                                                             int8_t *__restrict__ Wq, int64_t ldwq,
                                                             float *__restrict__ s_normal, float *__restrict__ s_outlier,
-                                                            float qmax)
+                                                            float qmax, bool scales_given)
 {
     __shared__ float red[8];
     const int j = blockIdx.x;
@@ -184,26 +261,32 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const float *__restr
     const int n_off = (K_o + 31) / 32 * 32;
     const int kp = (n_off + (K - K_o) + 127) / 128 * 128;
     const float *w = W + (size_t)j * ldw;
-    float a_o = 0.0f, a_n = 0.0f;
-    for (int k = tid; k < K; k += 256) {
-        const float a = fabsf(w[k]);
-        if (pos[k] < K_o) a_o = fmaxf(a_o, a);
-        else a_n = fmaxf(a_n, a);
-    }
-    a_o = wave_max(a_o);
-    a_n = wave_max(a_n);
-    if ((tid & 63) == 0) {
-        red[tid >> 6] = a_o;
-        red[4 + (tid >> 6)] = a_n;
-    }
-    __syncthreads();
-    a_o = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    a_n = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
-    const float so = a_o / qmax;     // qmax = 127 (INT8 codes) or 7 (INT4 codes)
-    const float sn = a_n / qmax;
-    if (tid == 0) {
-        s_outlier[j] = so;
-        s_normal[j] = sn;
+    float so, sn;
+    if (scales_given) {              // (uniform) the clip search has written this row's scales
+        so = s_outlier[j];
+        sn = s_normal[j];
+    } else {
+        float a_o = 0.0f, a_n = 0.0f;
+        for (int k = tid; k < K; k += 256) {
+            const float a = fabsf(w[k]);
+            if (pos[k] < K_o) a_o = fmaxf(a_o, a);
+            else a_n = fmaxf(a_n, a);
+        }
+        a_o = wave_max(a_o);
+        a_n = wave_max(a_n);
+        if ((tid & 63) == 0) {
+            red[tid >> 6] = a_o;
+            red[4 + (tid >> 6)] = a_n;
+        }
+        __syncthreads();
+        a_o = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        a_n = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
+        so = a_o / qmax;     // qmax = 127 (INT8 codes) or 7 (INT4 codes)
+        sn = a_n / qmax;
+        if (tid == 0) {
+            s_outlier[j] = so;
+            s_normal[j] = sn;
+        }
     }
     int8_t *out = Wq + (size_t)j * ldwq;
     for (int k = tid; k < K; k += 256) {
@@ -274,6 +357,7 @@ extern "C" void qarvd_default_detect_cfg(qarvd_detect_cfg *cfg)
     cfg->tau = 3.5;
     cfg->alpha = 1.2;
     cfg->align = 32;
+    cfg->clip_search = 0;
     cfg->forced_mask = nullptr;
 }
 
@@ -320,6 +404,8 @@ qarvd_status quantize_weight_impl(int bits, const float *W, int32_t N, int32_t K
     qarvd_default_detect_cfg(&c);
     if (cfg) c = *cfg;
     if (!c.forced_mask && (!(c.tau >= 0.0) || !(c.alpha >= 0.0) || c.align <= 0)) return QARVD_ERR_INVALID_ARG;
+    if (c.clip_search != 0 && c.clip_search != 1) return QARVD_ERR_INVALID_ARG;
+    if (c.clip_search && K > 16384) return QARVD_ERR_UNSUPPORTED;     // the search keeps the 20 largest magnitudes
     // The split is not known yet, so the row stride must hold the widest packed row the call can
     // produce: K rounded up to 128 when the aligned count is a multiple of 32 (no inner padding),
     // else the general worst case.
@@ -352,8 +438,12 @@ qarvd_status quantize_weight_impl(int bits, const float *W, int32_t N, int32_t K
         hipLaunchKernelGGL(select_by_rank_kernel, dim3(gK256), dim3(256), 0, st, ws.rank, K, ws.sc, ws.sel);
     }
     hipLaunchKernelGGL(build_perm_kernel, dim3(1), dim3(1024), 0, st, ws.sel, K, ws.sc, c.forced_mask ? 1 : 0, perm, ws.pos);
+    const float qmax = bits == 8 ? 127.0f : 7.0f;
+    if (c.clip_search)
+        hipLaunchKernelGGL(clip_search_kernel, dim3((2 * N + 63) / 64), dim3(64), 0, st, W, N, K, ldw, perm, ws.sc, qmax,
+                           s_normal, s_outlier);
     hipLaunchKernelGGL(quantize_rows_kernel, dim3(N), dim3(256), 0, st, W, N, K, ldw, ws.pos, ws.sc, codes, ldc, s_normal,
-                       s_outlier, bits == 8 ? 127.0f : 7.0f);
+                       s_outlier, qmax, c.clip_search != 0);
     if (v_out) QARVD_HIP_TRY(hipMemcpyAsync(v_out, ws.v, (size_t)K * 4, hipMemcpyDeviceToDevice, st));
     qarvd_status ls = qarvd_launch_status();
     if (ls != QARVD_OK) return ls;

@@ -50,7 +50,7 @@ def test_defaults_and_status_strings(lib):
     from paper_2605_21072_amd.binding import _DetectCfg
     cfg = _DetectCfg()
     lib.qarvd_default_detect_cfg(C.byref(cfg))
-    assert (cfg.tau, cfg.alpha, cfg.align, cfg.forced_mask) == (3.5, 1.2, 32, None)
+    assert (cfg.tau, cfg.alpha, cfg.align, cfg.clip_search, cfg.forced_mask) == (3.5, 1.2, 32, 0, None)
     assert lib.qarvd_status_string(0) == b"QARVD_OK"
     assert lib.qarvd_status_string(-2) == b"QARVD_ERR_UNSUPPORTED"
     assert lib.qarvd_gemm_num_variants() >= 1
