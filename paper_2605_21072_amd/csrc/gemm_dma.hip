@@ -392,10 +392,9 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
     // channels run through the dual kernel, or the single-accumulator build).
     auto epilogue = [&](auto haso_tag) {
         constexpr bool HASO = decltype(haso_tag)::value;
-        constexpr bool J_OUTER = false;     // see above
         constexpr int NBLK = TM * TN;
-        auto blk_i = [&](int b) { return J_OUTER ? b % TM : b / TN; };
-        auto blk_j = [&](int b) { return J_OUTER ? b / TM : b % TN; };
+        auto blk_i = [&](int b) { return b / TN; };
+        auto blk_j = [&](int b) { return b % TN; };
 
         v4i pend[2];
         int pend_voff = 0, pend_soff = 0;
@@ -464,7 +463,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
 #pragma unroll
         for (int b = 0; b < NBLK; ++b) {
             const int i = blk_i(b), j = blk_j(b);
-            if (!J_OUTER || i == 0) load_cols(j);
+            load_cols(j);
             v16i ao;
             if constexpr (AO_AHEAD) {
                 ao = ao_next;
