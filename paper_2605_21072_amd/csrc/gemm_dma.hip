@@ -37,6 +37,11 @@
 //     wave-private swizzled LDS patch (32 rows x 64 B) and stored as 16-byte chunks, 16 rows x 64 B
 //     per instruction.  The epilogue waits for the prefetched stages once, before its first store,
 //     so that no stage wait of the next tile has output stores ahead of it in the memory counter.
+//     The epilogue is software-pipelined: a patch is read back as soon as it is complete and stored
+//     after the next block's arithmetic, and the next block's outlier MFMAs start before the current
+//     block's arithmetic.
+//   * INT8 output (chained layers): optional GELU and the next layer's static-scale quantization on
+//     the fp32 result, four codes per dword, two 32-column blocks per 64-byte patch row.
 #include <algorithm>
 
 #include "gemm_dma_common.h"
