@@ -27,6 +27,9 @@
  *   dual-scale concat [outlier|normal]   Sec. 3.2, Eq. (dual_scale)
  *   per-channel (per output row) weights Sec. 4.1 "Quantization Implementation"
  *   two kernels: act-quant, GEMM+dequant App. "Quantization Kernels and Extra Cost Analysis"
+ *   4-bit weights (W4A8)                 Sec. 4.2 (result tables), Eq. (quantization) at b = 4
+ *   static per-tensor activation scale   Sec. 4.1 "Quantization Implementation"
+ *   percentile-clip scale initialisation Sec. 4.1 "Quantization Implementation"
  *
  * Readings taken where the paper is silent (each is listed in the design notes):
  *   median of an even-length vector = mean of the two middle values;
@@ -34,7 +37,10 @@
  *   outlier block first, ascending channel index inside each block;
  *   weight scale = block absmax / 127 per output row, round-half-even, clip [-127,127];
  *   activation scale = per-token absmax / 127 over all K channels (dynamic);
- *   a zero scale quantizes to 0; absent bias is +0.0f.
+ *   a zero scale quantizes to 0; absent bias is +0.0f;
+ *   chained layers: GELU (tanh form) in fp32 with a fixed operation sequence, then the next layer's
+ *   static scale; percentile clip: linear-interpolated quantile of |w| per row and block, squared
+ *   error summed in double in packed order, the larger percentile on a tie.
  *
  * Parity status: every function below is pinned by tests/test_oracle_*.py
  * against brute force, library routines (numpy / scipy) and invariants.
