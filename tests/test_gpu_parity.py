@@ -244,6 +244,25 @@ def test_gemm_extreme_accumulator_values():
     assert check_y(Y, ref) == 0
 
 
+@pytest.mark.parametrize("variant", [0, 1, 9, 11, 17])
+def test_gemm_longest_k_accumulators_at_the_int32_edge(variant):
+    """K at the library's limit (K * 127^2 must stay below 2^31): every product +-16129, all of one sign per
+    output, so the normal-range sum ends within 0.02 % of INT32_MAX / INT32_MIN."""
+    K = 133120                                           # largest multiple of 128 not above the limit of 133143
+    M, N, K_o = 40, 48, 32
+    Xq = np.full((M, K), 127, np.int8)
+    Wq = np.full((N, K), 127, np.int8)
+    Wq[1::2] = -127
+    one_m, one_n = np.ones(M, np.float32), np.ones(N, np.float32)
+    ref = oracle.dual_gemm(Xq, one_m, Wq, one_n, one_n, None, K_o)
+    assert int(ref["acc_n"][0, 0]) == 16129 * (K - K_o) > 2 ** 31 - 2 ** 20 and int(ref["acc_n"][0, 1]) == -16129 * (K - K_o)
+    w = q.DualScaleWeight(dev(_pack(Wq, K, K_o)), dev(one_n), dev(one_n), None, K_o, N, K)
+    Y, an, ao = q.w8a8_dual_gemm(dev(_pack(Xq, K, K_o)), dev(one_m), w, None, M, torch.float32, debug_acc=True, variant=variant)
+    torch.cuda.synchronize()
+    assert np.array_equal(an.cpu().numpy(), ref["acc_n"]) and np.array_equal(ao.cpu().numpy(), ref["acc_o"])
+    assert check_y(Y, ref) == 0
+
+
 # ------------------------------------------------------------- whole layer, end to end
 
 def run_layer_gpu(L, out_dtype, forced_mask=None, variant=0):
