@@ -25,6 +25,10 @@ const Variant kVariants[] = {
     {"lds-direct 128x256 (8 waves, 4 stages) single", 128, 256, 0, true, launch_dma<128, 256, 2, 4, 4, false>},
     {"16x16x64 256x224 (8 waves, 4 stages) dual", 256, 224, 128, true, launch_mfma16<256, 224, 4, 2, 4, true>},
     {"16x16x64 256x224 (8 waves, 4 stages) single", 256, 224, 0, true, launch_mfma16<256, 224, 4, 2, 4, false>},
+    {"lds-direct 64x128 (4 waves, 5 stages) dual", 64, 128, 128, true, launch_dma<64, 128, 2, 2, 5, true>},
+    {"lds-direct 64x128 (4 waves, 5 stages) single", 64, 128, 0, true, launch_dma<64, 128, 2, 2, 5, false>},
+    {"lds-direct 64x64 (4 waves, 6 stages) dual", 64, 64, 128, true, launch_dma<64, 64, 2, 2, 6, true>},
+    {"lds-direct 64x64 (4 waves, 6 stages) single", 64, 64, 0, true, launch_dma<64, 64, 2, 2, 6, false>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -50,22 +54,27 @@ bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)
 // tile that has its CU to itself (two four-wave workgroups sharing a CU each run at half speed, which
 // the ceil over 256 CUs already accounts for).  The 256x256 tile has the cheapest iteration per MAC and
 // wins when N is wide; the 128x256 eight-wave tile fills the chip when N = 1536; the 128x128 tile wins
-// for short M; the 16x16x64 kernel overtakes the 256x256 one once K is long enough to amortise its
-// dearer epilogue, because the chip holds a higher clock under its MFMA mix.
+// for short M, and the 64x64 / 64x128 tiles when even those would leave most CUs without a tile (M of a few
+// hundred rows with N = 1536: 24 us instead of 37 us at K = 8960); the 16x16x64 kernel overtakes the
+// 256x256 one once K is long enough to amortise its dearer epilogue.
 int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
 {
     const bool dual = g.n_off > 0;
     if (g.n_off <= 128 && vector_out_ok(g, ydt)) {
         struct Cand { int variant, bm, bn; double c, a, b; };
-        const Cand cand[5] = {{dual ? 11 : 12, 256, 256, 2.2, 8.9, 0.688},
+        const Cand cand[7] = {{dual ? 11 : 12, 256, 256, 2.2, 8.9, 0.688},
                               {dual ? 17 : 18, 256, 224, 4.0, 11.5, 0.621},
                               {dual ? 15 : 16, 128, 256, 5.0, 2.75, 0.490},
                               {dual ? 13 : 14, 256, 128, 5.0, 3.0, 0.508},
-                              {dual ? 9 : 10, 128, 128, 2.0, 1.5, 0.309}};
+                              {dual ? 9 : 10, 128, 128, 2.0, 1.5, 0.309},
+                              {dual ? 19 : 20, 64, 128, 2.0, 0.8, 0.187},
+                              {dual ? 21 : 22, 64, 64, 2.0, 0.77, 0.152}};
         const double T = g.kp / 64;
         int best = cand[0].variant;
         double best_cost = 1e300;
+        const long tiles128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128);
         for (const Cand &c : cand) {
+            if (c.bm == 64 && tiles128 > 256) continue;     // the small tiles only pay while 128x128 tiles leave CUs empty
             const long tiles = (long)((g.M + c.bm - 1) / c.bm) * ((g.N + c.bn - 1) / c.bn);
             const double cost = c.c + (double)((tiles + 255) / 256) * (c.a + c.b * T);
             if (cost < best_cost) {

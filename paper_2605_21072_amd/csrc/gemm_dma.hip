@@ -626,6 +626,8 @@ QARVD_INST(128, 256, 2, 4, 4)
 QARVD_INST(256, 128, 2, 2, 3)
 QARVD_INST(192, 128, 2, 2, 3)
 QARVD_INST(128, 128, 2, 2, 4)
+QARVD_INST(64, 128, 2, 2, 5)
+QARVD_INST(64, 64, 2, 2, 6)
 QARVD_INST_W4(256, 256, 2, 4, 4)
 QARVD_INST_W4(128, 128, 2, 2, 4)
 

@@ -197,7 +197,7 @@ def _pack(a, K, K_o):
 
 
 def _variants():
-    return list(range(0, 20))
+    return list(range(0, 24))
 
 
 @pytest.mark.parametrize("variant", _variants())
