@@ -115,6 +115,26 @@ def test_quant_act_parity(M, K, c, dtype):
     assert np.array_equal(logical(Xq_g, K, K_o), Xq_o)
 
 
+@pytest.mark.parametrize("K", [1536, 8960])
+def test_quant_act_perm_at_a_4_byte_aligned_address(K):
+    """perm is fetched 16 bytes per lane when it is 16-byte aligned; a permutation that starts one element into
+    a buffer takes the scalar path and must give the same bytes."""
+    rng = np.random.default_rng(K)
+    M, c = 21, 37
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    sel = np.zeros(K, np.uint8)
+    sel[rng.choice(K, c, replace=False)] = 1
+    perm, K_o = oracle.build_perm(sel)
+    Xq_o, sx_o = oracle.quant_act(X, perm)
+    buf = torch.zeros(K + 1, dtype=torch.int32, device="cuda")
+    buf[1:] = dev(perm)
+    assert buf[1:].data_ptr() % 16 == 4
+    Xq_g, sx_g = q.quant_act(dev(X), buf[1:], K_o)
+    torch.cuda.synchronize()
+    assert np.array_equal(sx_g.cpu().numpy().view(np.uint32), sx_o.view(np.uint32))
+    assert np.array_equal(logical(Xq_g, K, K_o), Xq_o)
+
+
 @pytest.mark.parametrize("K,amax", [(1536, 100.3), (8960, 3.7), (1000, 127.0), (250, 0.011)])
 def test_quant_act_rounding_boundaries(K, amax):
     """Values sitting on and next to the half-integer rounding boundaries of x / s: the kernel's
