@@ -101,6 +101,56 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert qw(p, 4, 128, 128, None, p, 128, p, p, p, C.byref(ko), null, C.c_void_p(0x1010), 1 << 20, null) == WORKSPACE
 
 
+def test_bad_arguments_of_the_widened_entry_points(lib):
+    from paper_2605_21072_amd.binding import _DetectCfg
+    p = C.c_void_p(0x1000)          # never dereferenced: validation fails first
+    null = None
+    INVALID, UNSUPPORTED = -1, -2
+    f = C.c_float
+    # chained-layer GEMM: Xq, ldxq, s_x, Wq, ldwq, s_n, s_o, bias, M, N, K, K_o, act, out_scale, Y8, ldy8, variant, stream
+    q8 = lib.qarvd_w8a8_dual_gemm_q8
+    ok = [p, 128, p, p, 128, p, p, null, 4, 16, 128, 0, 0, f(0.1), p, 16, 0, null]
+
+    def q8_with(i, v):
+        a = list(ok)
+        a[i] = v
+        return q8(*a)
+
+    assert q8_with(14, null) == INVALID                       # no output
+    assert q8_with(12, 5) == INVALID                          # unknown activation
+    for bad in (0.0, -1.0, float("nan"), float("inf"), 1e-38):
+        assert q8_with(13, f(bad)) == INVALID
+    assert q8_with(15, 8) == INVALID                          # ldy8 < N
+    assert q8_with(16, 99) == INVALID                         # unknown variant
+    assert q8_with(9, 24) == INVALID                          # N = 24 > ldy8 = 16
+    a = list(ok)
+    a[9], a[15] = 24, 32
+    assert q8(*a) == UNSUPPORTED                              # N not a multiple of 16
+    assert q8_with(14, C.c_void_p(0x1008)) == UNSUPPORTED     # output not 16-byte aligned
+    # INT4 GEMM: ldwq4 is in bytes, at least half the packed extent
+    w4 = lib.qarvd_w4a8_dual_gemm
+    ok4 = [p, 128, p, p, 64, p, p, null, 4, 8, 128, 0, p, 1, 8, null, null, 0, null]
+    a = list(ok4)
+    a[4] = 32
+    assert w4(*a) == INVALID
+    a = list(ok4)
+    a[17] = 9
+    assert w4(*a) == INVALID
+    a = list(ok4)
+    a[9], a[14] = 12, 12
+    assert w4(*a) == UNSUPPORTED                              # N % 8 != 0: no fast path, and INT4 has no other
+    # percentile-clip search: flag values and its K limit
+    ko = C.c_int32(0)
+    cfg = _DetectCfg()
+    lib.qarvd_default_detect_cfg(C.byref(cfg))
+    cfg.clip_search = 2
+    qw = lib.qarvd_quantize_weight
+    assert qw(p, 4, 128, 128, C.byref(cfg), p, 128, p, p, p, C.byref(ko), null, p, 1 << 20, null) == INVALID
+    cfg.clip_search = 1
+    assert qw(p, 4, 16512, 16512, C.byref(cfg), p, 16512, p, p, p, C.byref(ko), null, p, 1 << 30, null) == UNSUPPORTED
+    assert lib.qarvd_q8_gemm_num_variants() >= 1 and lib.qarvd_w4_gemm_num_variants() >= 1
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     import paper_2605_21072_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
