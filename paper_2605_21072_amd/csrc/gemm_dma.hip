@@ -210,6 +210,19 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks][j], xf[ks][i], acc[i][j], 0, 0, 0);
     };
 
+    // Last row of tiles: 32-row blocks that lie entirely below the matrix are skipped (their outputs are dropped
+    // anyway); the power they would draw is what limits the clock of the whole chip.
+    int i_lim = TM;
+    auto mma_r = [&](int ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            if (i < i_lim) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks][j], xf[ks][i], acc[i][j], 0, 0, 0);
+            }
+    };
+
     // Instruction-order hints for the scheduler (masks: 0x008 MFMA, 0x100 LDS read, 0x020 VMEM read):
     // one fragment read after each of the first TM+TN MFMAs, and in the second half-iteration the
     // LDS-direct loads spread over the following MFMAs.
@@ -303,6 +316,22 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
     load_frags(smem + base * STG, 0);
     int stage = base;
     long long p_t0 = QARVD_PROF ? clock64() : 0;
+    i_lim = min(TM, max(0, (min(BM, g.M - m0) - wm * G::WTM + 31) / 32));
+    if (i_lim < TM) {                            // ragged tile: same steps, unneeded row blocks left out
+#pragma unroll 1
+        for (int it = 0; it < T - AHEAD; ++it) {
+            const unsigned char *sb = smem + stage * STG;
+            const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
+            load_frags(sb, 1);
+            mma_r(0);
+            wait_vmcnt<(AHEAD - 2) * G::NLOAD>();
+            __builtin_amdgcn_s_barrier();
+            load_frags(smem + nstage * STG, 0);
+            issue(seq(it + AHEAD), stage >= 1 ? stage - 1 : NSTAGE - 1);
+            mma_r(1);
+            stage = nstage;
+        }
+    } else
     for (int it = 0; it < T - AHEAD; ++it) {     // steady state: every tile here is a normal tile
         const unsigned char *sb = smem + stage * STG;
         const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
@@ -340,14 +369,14 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
         const int hs = it - Tn;                   // >= 0: head tile number
         const bool use0 = hs < 0 || 2 * hs >= o_steps, use1 = hs < 0 || 2 * hs + 1 >= o_steps;
         load_frags(sb, 1);
-        if (use0) mma(0);
+        if (use0) mma_r(0);
         if (it + 1 < T) {
             if (AHEAD >= 3 && T - 2 - it >= 1) wait_vmcnt<G::NLOAD>();
             else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
             load_frags(smem + nstage * STG, 0);
         }
-        if (use1) mma(1);
+        if (use1) mma_r(1);
         stage = nstage;
     }
     long long p_t1 = QARVD_PROF ? clock64() : 0;
