@@ -138,6 +138,8 @@ def main():
             gemm_us[i] += 1e3 * ev[s_i][2 * i + 1].elapsed_time(ev[s_i][2 * i + 2])
     quant_us /= args.steps
     gemm_us /= args.steps
+    # what the per-launch events add: the instrumented pass against the plain timed pass, per launch
+    event_overhead_us = (float(quant_us.sum() + gemm_us.sum()) - 1e3 * ms_per_step) / (2 * nl)
 
     # ---- bf16 comparator: the vendor GEMM a user would otherwise call ----------------------
     bf16_us = [None] * nl
@@ -237,6 +239,7 @@ def main():
                            % (args.config, nl, specs[0].M),
                            layers=nl, launches_per_step=2 * nl, out_dtype="bf16", gemm_variant=args.variant),
                frac_int8_peak=round(value / PEAK_INT8_TOPS, 4),
+               event_overhead_us_per_launch=round(event_overhead_us, 2),
                roofline=roofline, quant_act_roofline=quant_roof)
     if tgt:
         t = [per_layer[i] for i in tgt]
