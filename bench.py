@@ -408,11 +408,26 @@ def main():
                              want_acc=False, want_f32=False, want_bf16=True)
             cpu_t += time.perf_counter() - t1
             cpu_ops += 2.0 * s.macs
+        # and on ONE host thread, the single config-1 layer (M=256, 1536 -> 1536)
+        n_thr = oracle.num_threads()
+        s1 = wl.config_layers(1)[0]
+        L1 = wl.make_layer(s1)
+        q1 = oracle.quantize_weight(L1["W"])
+        oracle.set_num_threads(1)
+        t1 = time.perf_counter()
+        Xq1, sx1 = oracle.quant_act(L1["X"], q1["perm"])
+        oracle.dual_gemm(Xq1, sx1, q1["Wq"], q1["s_normal"], q1["s_outlier"], L1["bias"], q1["K_o"],
+                         want_acc=False, want_f32=False, want_bf16=True)
+        one_t = time.perf_counter() - t1
+        oracle.set_num_threads(n_thr)
+        one_thread = dict(value=round(2.0 * s1.macs / one_t / 1e12, 5), unit="TOPS", cores=1, seconds=round(one_t, 3),
+                          sample="config 1 (M=256, 1536 -> 1536), quant_act + dual_gemm")
         out["cpu_baseline"] = dict(value=round(cpu_ops / cpu_t / 1e12, 5), unit="TOPS", cores=oracle.num_threads(),
                                    kind="oracle", seconds=round(cpu_t, 2),
                                    sample="%d of the step's %d layers (q,k,v,o,ffn_up,ffn_down at M=%d with 16 and with 64 "
                                           "planted outliers), quant_act + dual_gemm, full size"
-                                          % (len(smp), len(layers), smp[0]["spec"].M))
+                                          % (len(smp), len(layers), smp[0]["spec"].M),
+                                   one_thread=one_thread)
     out["layers"] = per_layer
     print(json.dumps(out))
 
