@@ -56,7 +56,10 @@ bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)
 // wins when N is wide; the 128x256 eight-wave tile fills the chip when N = 1536; the 128x128 tile wins
 // for short M, and the 64x64 / 64x128 tiles when even those would leave most CUs without a tile (M of a few
 // hundred rows with N = 1536: 24 us instead of 37 us at K = 8960); the 16x16x64 kernel overtakes the
-// 256x256 one once K is long enough to amortise its dearer epilogue.
+// 256x256 one once K is long enough to amortise its dearer epilogue.  The constants of the two eight-wave
+// half tiles come from timings inside a sequence of layers, where the activations have just been written and
+// the weights come from memory: there the tall 256x128 tile (each weight panel fetched by half as many tiles)
+// beats the wide 128x256 one by 9 %, although launched back to back on cached operands it is 2 % slower.
 int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
 {
     const bool dual = g.n_off > 0;
@@ -64,8 +67,8 @@ int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
         struct Cand { int variant, bm, bn; double c, a, b; };
         const Cand cand[7] = {{dual ? 11 : 12, 256, 256, 2.2, 8.9, 0.688},
                               {dual ? 17 : 18, 256, 224, 4.0, 11.5, 0.621},
-                              {dual ? 15 : 16, 128, 256, 5.0, 2.75, 0.490},
-                              {dual ? 13 : 14, 256, 128, 5.0, 3.0, 0.508},
+                              {dual ? 15 : 16, 128, 256, 5.0, 2.75, 0.550},
+                              {dual ? 13 : 14, 256, 128, 4.5, 2.0, 0.505},
                               {dual ? 9 : 10, 128, 128, 2.0, 1.5, 0.309},
                               {dual ? 19 : 20, 64, 128, 2.0, 0.8, 0.187},
                               {dual ? 21 : 22, 64, 64, 2.0, 0.77, 0.152}};
