@@ -193,6 +193,10 @@ def test_quant_act_static_parity(K, dtype):
     Xq_g = q.quant_act_static(Xd, dev(perm), K_o, float(s))
     torch.cuda.synchronize()
     assert np.array_equal(logical(Xq_g, K, K_o), oracle.quant_act_static(X, s, perm))
+    Xq_0 = q.quant_act_static(Xd, dev(perm), K_o, 0.0)          # a zero scale gives zero codes
+    torch.cuda.synchronize()
+    assert np.array_equal(logical(Xq_0, K, K_o), oracle.quant_act_static(X, np.float32(0.0), perm))
+    assert not Xq_0.any()
 
 
 # ----------------------------------------------------------------------------- GEMM

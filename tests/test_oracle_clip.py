@@ -47,6 +47,9 @@ def test_small_example_by_hand():
     w = np.float32([2.0, -100.0, 1.0, 3.0])
     r = oracle.clip_search(w, 127.0)
     assert np.allclose(r["clip"], [3 + 0.997 * 97, 3 + 0.9997 * 97, 3 + 0.99997 * 97], rtol=2e-7)
+    # an empty block (no outlier channel) has scale 0 and reports the least-clipping percentile
+    e = oracle.clip_search(np.zeros(0, np.float32), 127.0)
+    assert float(e["s"]) == 0.0 and e["choice"] == 2
 
 
 def test_each_percentile_can_win():

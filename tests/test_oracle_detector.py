@@ -54,6 +54,17 @@ def test_column_norms_closed_form():
     assert oracle.column_norms(W).tolist() == [5.0, 2.0, 7.0]
 
 
+def test_column_norms_are_summed_in_double():
+    # 4096^2 = 2^24: a single-precision running sum cannot absorb the 4095 ones that follow (it would
+    # return exactly 4096), the double sum is the integer 16781311 and its root rounds to 4096.5
+    W = np.ones((4096, 2), np.float32)
+    W[0, 0] = 4096.0
+    W[:, 1] = 0.25
+    v = oracle.column_norms(W)
+    assert float(v[0]) == float(np.float32(math.sqrt(4096 ** 2 + 4095))) == 4096.5
+    assert float(v[1]) == 16.0
+
+
 def test_detector_hand_worked_even_length():
     # v = 1,2,3,4: median 2.5; |v-med| = 1.5,.5,.5,1.5 -> MAD 1.0
     flag, st = oracle.detect(np.array([1, 2, 3, 4], np.float32), tau=3.5, alpha=1.2)

@@ -102,6 +102,8 @@ def test_static_activation_scale_variant():
     ref = np.clip(np.rint(X / s), -127, 127).astype(np.int8)[:, perm]
     assert np.array_equal(Xq, ref)
     assert np.abs(Xq).max() == 127                 # clip fires: 3-sigma values exceed 127*0.02
+    # a zero scale gives the code 0, not the clipped infinity x / 0 would round to
+    assert not oracle.quant_act_static(X, np.float32(0.0), perm).any()
 
 
 def test_weight_scales_and_blocks():
