@@ -12,12 +12,16 @@
  *
  * Conventions
  *   - Every pointer is DEVICE memory unless its comment says "host".  The caller owns every
- *     buffer; the library allocates nothing and keeps no state between calls.
+ *     buffer; the library allocates nothing.  The only state it keeps between calls is what it
+ *     has learnt about a device (its compute-unit count, which kernels already had their LDS
+ *     limit raised).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *   - W is fp32 [N,K] row-major: N = d_out rows, K = d_in input channels.  X is [M,K] row-major
  *     (tokens x channels).  Y is [M,N] row-major.  Leading dimensions are in ELEMENTS.
  *   - Functions return a qarvd_status and never abort or throw.  Arguments are validated on
- *     the host before anything is launched; on error nothing has been written.
+ *     the host before anything is launched: with INVALID_ARG, UNSUPPORTED or WORKSPACE nothing
+ *     has been written.  QARVD_ERR_HIP reports a failed HIP call or launch and can come after
+ *     earlier kernels of the same call have run; the outputs are then unspecified.
  *
  * Packed K axis (the layout both INT8 operands share)
  *   Position p of a packed row holds input channel perm[p].  With K_o outlier channels:
@@ -58,8 +62,8 @@ typedef enum { QARVD_F32 = 0, QARVD_BF16 = 1 } qarvd_dtype;
  * Detector parameters (Sec. 3.2, Eq. (new_threshold): tau = 3.5, alpha = 1.2; Fig. "outlier
  * patterns" caption: the outlier count is aligned to a multiple of 32).
  *   clip_search  0: each scale is the block's absmax / qmax (Eq. (quantization)).  1: percentile-clip
- *                initialisation (Sec. 4.1 "Quantization Implementation": the clipping percentile is
- *                searched over {0.999, 0.9999, 0.99999}), data-free, per output row and block: the
+ *                initialisation (Sec. 4.1, quantization implementation: the scale is initialised at the
+ *                best of the clipping percentiles 0.999, 0.9999 and 0.99999), data-free, per output row and block: the
  *                linear-interpolated p-quantile of |w| (h = (n-1) p, in double, rounded to float) over
  *                qmax is a candidate scale; the one with the smallest squared quantization error
  *                sum (fmaf(-s, q, w))^2 (summed in double in packed order) wins, the larger percentile
@@ -108,7 +112,9 @@ size_t qarvd_quantize_weight_workspace(int32_t N, int32_t K);
  *
  *   W          in   f32 [N, ldw]
  *   cfg        in   host; NULL = defaults
- *   Wq         out  i8  [N, ldwq] packed (see above); ldwq >= qarvd_packed_k(K, -1), multiple of 16
+ *   Wq         out  i8  [N, ldwq] packed (see above); ldwq a multiple of 16 and >= qarvd_packed_k(K, -1)
+ *                   (K rounded up to 128 is enough when the outlier block cannot need padding: cfg->align a
+ *                   multiple of 32 and no forced_mask)
  *   s_normal   out  f32 [N]     s_outlier  out f32 [N]  (0 for an empty block)
  *   perm       out  i32 [K]     gather index: packed position p reads channel perm[p]
  *   K_o_host   out  HOST int32

@@ -251,16 +251,18 @@ def gelu_tanh(x):
     return np.array([lib.oracle_gelu_tanh(float(v)) for v in x.ravel()], np.float32).reshape(x.shape)
 
 
-def dual_gemm_q8(Xq, s_x, Wq, s_normal, s_outlier, bias, K_o, s_out, act=0):
-    """Dual GEMM whose epilogue quantizes for the next layer.  Returns int8 [M, N]."""
+def dual_gemm_q8(Xq, s_x, Wq, s_normal, s_outlier, bias, K_o, s_out, act=0, want_act=False):
+    """Dual GEMM whose epilogue quantizes for the next layer.  Returns int8 [M, N]; with want_act also
+    the fp32 value each code was rounded from (after the activation)."""
     Xq = np.ascontiguousarray(Xq, dtype=np.int8)
     Wq = np.ascontiguousarray(Wq, dtype=np.int8)
     M, K = Xq.shape
     N = Wq.shape[0]
     b = None if bias is None else _f32(bias)
     Y8 = np.empty((M, N), np.int8)
+    A = np.empty((M, N), np.float32) if want_act else None
     _check(_load().oracle_dual_gemm_q8(_p(Xq, C.c_int8), _p(_f32(s_x), C.c_float), _p(Wq, C.c_int8),
                                        _p(_f32(s_normal), C.c_float), _p(_f32(s_outlier), C.c_float),
                                        _p(b, C.c_float), M, N, K, int(K_o), int(act), C.c_float(float(s_out)),
-                                       _p(Y8, C.c_int8)))
-    return Y8
+                                       _p(Y8, C.c_int8), _p(A, C.c_float)))
+    return (Y8, A) if want_act else Y8

@@ -538,40 +538,18 @@ int oracle_dual_gemm(const int8_t *Xq, const float *s_x, const int8_t *Wq, const
 /* ----------- chained layers: the epilogue quantizes for the next layer (static scale) */
 
 /*
- * GELU, tanh form, in fp32 with every operation spelled out so that any IEEE-754 machine gets the
- * same bits:  gelu(x) = 0.5 x (1 + tanh(u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
- *           = x * sigma(2u),                  sigma(z) = 1 / (1 + exp(-z)).
- * exp(-z) = 2^t with t = -z log2(e) = x (C0 + C1 x^2), C0 = -2 log2(e) sqrt(2/pi), C1 = 0.044715 C0
- * (the constants multiplied out in double, rounded once), clamped to [-125, 125], split as
- * n = rint(t), f = t - n in [-1/2, 1/2]; 2^f = exp(f ln 2) by its Taylor polynomial of degree 7
- * (relative error < 1e-8);
- * the power of two goes into the exponent field.  The paper does not name the FFN activation; this is
- * the one the Wan-style DiT blocks of Sec. 4.1 use, and the exact arithmetic is this build's choice.
+ * GELU, tanh form, as it is defined:  gelu(x) = 0.5 x (1 + tanh(u)),  u = sqrt(2/pi) (x + 0.044715 x^3),
+ * evaluated in double precision with the C library's tanh and rounded once to float.  The paper does
+ * not name the FFN activation; this is the one the Wan-style DiT blocks of Sec. 4.1 use.  A GPU kernel
+ * evaluates the same function in fp32 by its own sequence of operations, so codes derived from the
+ * two may differ by one where a / s_out falls next to a rounding boundary; the parity tests state
+ * that rule.
  */
 float oracle_gelu_tanh(float x)
 {
-    float x2, inner, t, n, f, g, p, e, sg;
-    union { float f; int32_t i; } u;
-    x2 = x * x;
-    inner = fmaf(-0.102943240f, x2, -2.30220820f);
-    t = x * inner;
-    t = fminf(fmaxf(t, -125.0f), 125.0f);
-    n = rintf(t);
-    f = t - n;
-    g = f * 0.693147182f;
-    p = 1.0f / 5040.0f;
-    p = fmaf(p, g, 1.0f / 720.0f);
-    p = fmaf(p, g, 1.0f / 120.0f);
-    p = fmaf(p, g, 1.0f / 24.0f);
-    p = fmaf(p, g, 1.0f / 6.0f);
-    p = fmaf(p, g, 0.5f);
-    p = fmaf(p, g, 1.0f);
-    p = fmaf(p, g, 1.0f);
-    u.f = p;
-    u.i += (int32_t)n * (1 << 23);
-    e = u.f;
-    sg = 1.0f / (1.0f + e);
-    return x * sg;
+    double xd = (double)x;
+    double u = sqrt(2.0 / 3.14159265358979323846) * (xd + 0.044715 * xd * xd * xd);
+    return (float)(0.5 * xd * (1.0 + tanh(u)));
 }
 
 /*
@@ -579,10 +557,11 @@ float oracle_gelu_tanh(float x)
  * (same three operations), optionally through the activation (act = 1: GELU above), is quantized
  * with the NEXT layer's static per-tensor activation scale (Sec. 4.1 "per-tensor static
  * quantization for activations"; Eq. (quantization)):  Y8 = clip(rint(a / s_out), -127, 127).
+ * A_f32 (optional) receives a, the value that is quantized.
  */
 int oracle_dual_gemm_q8(const int8_t *Xq, const float *s_x, const int8_t *Wq, const float *s_normal,
                         const float *s_outlier, const float *bias, int M, int N, int K, int K_o,
-                        int act, float s_out, int8_t *Y8)
+                        int act, float s_out, int8_t *Y8, float *A_f32)
 {
     if (!Xq || !s_x || !Wq || !s_normal || !s_outlier || !Y8 || M <= 0 || N <= 0 || K <= 0 || K_o < 0 ||
         K_o > K || (act != 0 && act != 1) || !(s_out > 0.0f))
@@ -604,6 +583,8 @@ int oracle_dual_gemm_q8(const int8_t *Xq, const float *s_x, const int8_t *Wq, co
             r = fmaf(r, s_x[m], b);
             if (act == 1)
                 r = oracle_gelu_tanh(r);
+            if (A_f32)
+                A_f32[(size_t)m * N + j] = r;
             Y8[(size_t)m * N + j] = quantize_sym(r, s_out, 127.0f);
         }
     }

@@ -49,7 +49,7 @@ bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)
 
 // Heuristic: a three-constant cost model per LDS-direct variant, fitted to timings on MI355X over the
 // DiT shapes (M = 520..4680, N and K in {1536, 5120, 8960, 13824}):
-//     time ~ c + ceil(tiles / 256) * (a + b * T),     T = packed K / 64
+//     time ~ c + ceil(tiles / CUs) * (a + b * T),     T = packed K / 64   (constants in us, fitted on MI355X)
 // c is launch plus the first tile's lead-in, a a tile's epilogue and hand-over, b one K iteration of a
 // tile that has its CU to itself (two four-wave workgroups sharing a CU each run at half speed, which
 // the ceil over 256 CUs already accounts for).  The 256x256 tile has the cheapest iteration per MAC and
@@ -60,9 +60,16 @@ bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)
 // half tiles come from timings inside a sequence of layers, where the activations have just been written and
 // the weights come from memory: there the tall 256x128 tile (each weight panel fetched by half as many tiles)
 // beats the wide 128x256 one by 9 %, although launched back to back on cached operands it is 2 % slower.
+int device_cus()
+{
+    int cus = 0;
+    return (qarvd_current_device(nullptr, &cus) == QARVD_OK && cus > 0) ? cus : 256;
+}
+
 int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
 {
     const bool dual = g.n_off > 0;
+    const int cus = device_cus();      // rounds are counted over the CUs of the device the call runs on
     if (g.n_off <= 128 && vector_out_ok(g, ydt)) {
         struct Cand { int variant, bm, bn; double c, a, b; };
         const Cand cand[7] = {{dual ? 11 : 12, 256, 256, 2.2, 8.9, 0.688},
@@ -77,9 +84,9 @@ int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
         double best_cost = 1e300;
         const long tiles128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128);
         for (const Cand &c : cand) {
-            if (c.bm == 64 && tiles128 > 256) continue;     // the small tiles only pay while 128x128 tiles leave CUs empty
+            if (c.bm == 64 && tiles128 > cus) continue;     // the small tiles only pay while 128x128 tiles leave CUs empty
             const long tiles = (long)((g.M + c.bm - 1) / c.bm) * ((g.N + c.bn - 1) / c.bn);
-            const double cost = c.c + (double)((tiles + 255) / 256) * (c.a + c.b * T);
+            const double cost = c.c + (double)((tiles + cus - 1) / cus) * (c.a + c.b * T);
             if (cost < best_cost) {
                 best_cost = cost;
                 best = c.variant;
@@ -88,8 +95,8 @@ int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
         return best;
     }
     const long tiles_big = (long)((g.M + 255) / 256) * ((g.N + 127) / 128);
-    if (dual) return tiles_big >= 256 ? 1 : 2;
-    return tiles_big >= 256 ? 3 : 4;
+    if (dual) return tiles_big >= cus ? 1 : 2;
+    return tiles_big >= cus ? 3 : 4;
 }
 
 }  // namespace
@@ -189,8 +196,9 @@ extern "C" qarvd_status qarvd_w4a8_dual_gemm(const int8_t *Xq, int64_t ldxq, con
     if (variant == 0) {     // same cost model as the INT8 path, restricted to the two tiles built for INT4
         const double T = g.kp / 64;
         const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256), t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-        const double c256 = 2.2 + (double)((t256 + 255) / 256) * (8.9 + 0.688 * T);
-        const double c128 = 2.0 + (double)((t128 + 255) / 256) * (1.5 + 0.309 * T);
+        const int cus = device_cus();
+        const double c256 = 2.2 + (double)((t256 + cus - 1) / cus) * (8.9 + 0.688 * T);
+        const double c128 = 2.0 + (double)((t128 + cus - 1) / cus) * (1.5 + 0.309 * T);
         variant = c256 <= c128 ? 1 : 2;
     }
     const W4Variant &v = kW4Variants[variant - 1];
@@ -244,10 +252,11 @@ extern "C" qarvd_status qarvd_w8a8_dual_gemm_q8(const int8_t *Xq, int64_t ldxq, 
     if (variant == 0) {
         const double T = g.kp / 64;
         double best_cost = 1e300;
+        const int cus = device_cus();
         for (int i = 0; i < kNumQ8Variants; ++i) {
             const Q8Variant &c = kQ8Variants[i];
             const long tiles = (long)((M + c.BM - 1) / c.BM) * ((N + c.BN - 1) / c.BN);
-            const double cost = c.c + (double)((tiles + 255) / 256) * (c.a + c.b * T);
+            const double cost = c.c + (double)((tiles + cus - 1) / cus) * (c.a + c.b * T);
             if (cost < best_cost) { best_cost = cost; variant = i + 1; }
         }
     }

@@ -602,7 +602,8 @@ qarvd_status launch_one(const GemmArgs &g, hipStream_t st)
 {
     using G = Geo<BM, BN, WM, WN, NSTAGE, W4>;
     auto k = gemm_dma_kernel<BM, BN, WM, WN, NSTAGE, DUAL, DBG, OutT, W4>;
-    QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS_BYTES));
+    static unsigned long long lds_limit_raised = 0;      // one mask per instantiation, i.e. per kernel symbol
+    if (qarvd_status st_a = qarvd_raise_lds_limit_once(k, G::LDS_BYTES, lds_limit_raised); st_a != QARVD_OK) return st_a;
     constexpr int LDS_PER_CU = 160 * 1024;
     const int wg_per_cu = std::max(1, std::min(LDS_PER_CU / G::LDS_BYTES, (G::WAVES_PER_EU * 4) / G::NW));
     int grid = 0;

@@ -155,14 +155,8 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b)
 // so that the tiles one workgroup walks through stay on its XCD), at most one per tile
 inline qarvd_status persistent_grid(int tiles, int wg_per_cu, int *grid)
 {
-    int dev = 0;
-    QARVD_HIP_TRY(hipGetDevice(&dev));
-    static int cu_count[64] = {0};              // per device, filled on first use (same value from any thread)
-    int cus = (dev >= 0 && dev < 64) ? cu_count[dev] : 0;
-    if (cus <= 0) {
-        QARVD_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        if (dev >= 0 && dev < 64) cu_count[dev] = cus;
-    }
+    int cus = 0;
+    if (qarvd_status st = qarvd_current_device(nullptr, &cus); st != QARVD_OK) return st;
     const int slots = cus * wg_per_cu / 8 * 8;
     *grid = tiles < slots || slots < 8 ? tiles : slots;
     // More tiles than slots: the number of rounds is fixed by the slot count, so use only as many workgroups as

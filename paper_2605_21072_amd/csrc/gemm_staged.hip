@@ -158,11 +158,13 @@ qarvd_status launch_staged(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     const int grid = g.tiles_m * g.tiles_n;
     if (ydt == QARVD_BF16) {
         auto k = gemm_staged_kernel<BM, BN, WM, WN, DUAL, uint16_t>;
-        QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        static unsigned long long raised = 0;
+        if (qarvd_status s_a = qarvd_raise_lds_limit_once(k, (int)lds, raised); s_a != QARVD_OK) return s_a;
         hipLaunchKernelGGL(k, dim3(grid), dim3(TPB), lds, st, g);
     } else {
         auto k = gemm_staged_kernel<BM, BN, WM, WN, DUAL, float>;
-        QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        static unsigned long long raised = 0;
+        if (qarvd_status s_a = qarvd_raise_lds_limit_once(k, (int)lds, raised); s_a != QARVD_OK) return s_a;
         hipLaunchKernelGGL(k, dim3(grid), dim3(TPB), lds, st, g);
     }
     return qarvd_launch_status();

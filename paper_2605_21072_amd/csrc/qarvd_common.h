@@ -20,6 +20,38 @@ static inline qarvd_status qarvd_launch_status()
     return e == hipSuccess ? QARVD_OK : QARVD_ERR_HIP;
 }
 
+// Compute-unit count of the current device.  Device attributes are read once per device and kept for the life
+// of the process (the only state the library holds besides which kernels already had their LDS limit raised).
+static inline qarvd_status qarvd_current_device(int *dev_out, int *cus_out)
+{
+    static int cu_count[64] = {0};              // filled on first use; the same value from any thread
+    int dev = 0;
+    QARVD_HIP_TRY(hipGetDevice(&dev));
+    int cus = (dev >= 0 && dev < 64) ? cu_count[dev] : 0;
+    if (cus <= 0) {
+        QARVD_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        if (dev >= 0 && dev < 64) cu_count[dev] = cus;
+    }
+    if (dev_out) *dev_out = dev;
+    if (cus_out) *cus_out = cus;
+    return QARVD_OK;
+}
+
+// Raises a kernel's dynamic-LDS limit the first time it is launched on a device instead of on every launch
+// (the call costs microseconds of host time, as much as a short kernel).  `done` is one bit per device,
+// a static of the calling launcher, so there is one mask per kernel symbol; the attribute only ever grows.
+template <typename Kernel>
+static inline qarvd_status qarvd_raise_lds_limit_once(Kernel kernel, int bytes, unsigned long long &done)
+{
+    int dev = 0;
+    QARVD_HIP_TRY(hipGetDevice(&dev));
+    const unsigned long long bit = (dev >= 0 && dev < 64) ? (1ull << dev) : 0ull;
+    if (bit && (__atomic_load_n(&done, __ATOMIC_ACQUIRE) & bit)) return QARVD_OK;
+    QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    if (bit) __atomic_fetch_or(&done, bit, __ATOMIC_RELEASE);
+    return QARVD_OK;
+}
+
 static inline bool qarvd_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static inline int32_t qarvd_round_up(int32_t x, int32_t m) { return (x + m - 1) / m * m; }

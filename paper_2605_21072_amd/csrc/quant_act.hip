@@ -325,18 +325,10 @@ __global__ __launch_bounds__(TPB) void quant_act_generic_kernel(ActArgs a)
     }
 }
 
-int g_num_cu = 0;
 int num_cu()
 {
-    if (g_num_cu == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            g_num_cu = prop.multiProcessorCount;
-        else
-            g_num_cu = 256;
-    }
-    return g_num_cu;
+    int cus = 0;
+    return (qarvd_current_device(nullptr, &cus) == QARVD_OK && cus > 0) ? cus : 256;
 }
 
 constexpr size_t LDS_LIMIT = 160 * 1024;
@@ -346,8 +338,10 @@ qarvd_status launch_rows_one(const ActArgs &a, hipStream_t st)
 {
     const size_t lds = (IDENT ? 0 : 2 * (size_t)a.kp + (((size_t)a.K * sizeof(PosT) + 15) & ~(size_t)15)) + 2 * (NT / 64) * sizeof(float);
     auto kern = quant_act_rows_kernel<T, PosT, CH, NT, STATIC, IDENT>;
-    if (lds > 64 * 1024)
-        QARVD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    if (lds > 64 * 1024) {      // the limit goes to the hardware's whole LDS, once per kernel and device
+        static unsigned long long raised = 0;
+        if (qarvd_status s_a = qarvd_raise_lds_limit_once(kern, (int)LDS_LIMIT, raised); s_a != QARVD_OK) return s_a;
+    }
     int occ = (int)(LDS_LIMIT / (lds < 1024 ? 1024 : lds));
     const int occ_threads = 2048 / NT;
     occ = occ < 1 ? 1 : (occ > occ_threads ? occ_threads : occ);

@@ -53,3 +53,25 @@ def assert_weight_equal(g, o):
     assert np.array_equal(g["s_normal"].view(np.uint32), o["s_normal"].view(np.uint32))
     assert np.array_equal(g["s_outlier"].view(np.uint32), o["s_outlier"].view(np.uint32))
     assert np.array_equal(g["Wq"], o["Wq"])
+
+
+def assert_q8_codes(got, ref, a, s_out, act):
+    """Parity rule of the chained epilogue's INT8 codes.  Without an activation the code is a function of
+    the (bit-exact) fp32 result alone: equal.  With GELU the oracle rounds the double-precision definition
+    once, the kernel evaluates the same function in fp32 by its own operation sequence (within
+    2e-7 + 1.1e-6 |a| of the definition), so the codes must be equal wherever the oracle's a / s_out is
+    farther than that bound (plus the quotients' own rounding) from every rounding boundary k + 1/2, and
+    may differ by one next to a boundary.  Returns the number of codes that differ."""
+    got, ref = np.asarray(got), np.asarray(ref)
+    if not act:
+        assert np.array_equal(got, ref)
+        return 0
+    qd = a.astype(np.float64) / np.float64(np.float32(s_out))
+    dist = np.abs(qd - np.floor(qd) - 0.5)
+    eps = (4e-7 + 2e-6 * np.abs(a.astype(np.float64))) / np.float64(np.float32(s_out)) + 1e-4
+    diff = np.abs(got.astype(np.int32) - ref.astype(np.int32))
+    assert np.all(diff[dist > eps] == 0), "codes differ away from every rounding boundary"
+    assert diff.max() <= 1, "codes more than one apart"
+    n = int(np.count_nonzero(diff))
+    assert n <= max(2, 2e-3 * diff.size), "too many codes next to a boundary differ: %d of %d" % (n, diff.size)
+    return n

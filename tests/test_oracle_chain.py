@@ -15,10 +15,19 @@ def gelu64(x):
 
 
 def test_gelu_matches_the_tanh_definition_in_double():
+    """The oracle's GELU is the tanh form evaluated in double and rounded once.  Pinned to torch's own
+    tanh-approximate GELU in float64 (a library routine, not a retyped formula), to two values worked
+    by hand, and to properties of the function."""
+    import torch
     x = np.concatenate([np.linspace(-12, 12, 4801), np.array([0.0, 1e-6, -1e-6, 1e-3, 30.0, -30.0, 100.0, -100.0])]).astype(np.float32)
     g = oracle.gelu_tanh(x)
-    ref = gelu64(x)
-    assert np.all(np.abs(g - ref) <= 2e-7 + 1e-6 * np.abs(ref))
+    lib = torch.nn.functional.gelu(torch.from_numpy(x.astype(np.float64)), approximate="tanh").numpy()
+    assert np.all(np.abs(g - lib) <= 6.1e-8 * np.abs(lib) + 4e-15)       # half an fp32 ulp of the double result (+ the
+    #                                  cancellation of 1 + tanh(u) in double, deep in the negative tail)
+    assert np.all(np.abs(lib - gelu64(x)) <= 1e-14 * np.maximum(1.0, np.abs(lib)))
+    # tanh(sqrt(2/pi) * 1.044715) = tanh(0.83354...) = 0.682419...: gelu(1) = 0.841192, gelu(-1) = gelu(1) - 1
+    assert abs(float(oracle.gelu_tanh(np.float32([1.0]))[0]) - 0.8411919906) < 5e-8
+    assert abs(float(oracle.gelu_tanh(np.float32([-1.0]))[0]) + 0.1588080094) < 2e-8
     assert oracle.gelu_tanh(np.float32([0.0]))[0] == 0.0
     big = np.float32([9.0, 20.0, 100.0])
     assert np.array_equal(oracle.gelu_tanh(big), big)                  # saturates to the identity exactly
