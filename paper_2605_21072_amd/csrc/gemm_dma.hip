@@ -312,6 +312,14 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
     if (rest_pending) {             // (fetch before the stage loads: the waits count those from the youngest)
         for (int p = PF; p < AHEAD; ++p)
             if (p < T) issue(seq(p), (base + p) % NSTAGE);
+        if (PF == 0) {
+            // No stage of this tile could be prefetched under the previous epilogue (three stages, two of them
+            // head tiles, the third holding the patches): its first stage was issued just now and has to land,
+            // for every wave, before the first fragment read.
+            if (T >= AHEAD) wait_vmcnt<(AHEAD - 1) * G::NLOAD>();
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+        }
     }
     load_frags(smem + base * STG, 0);
     int stage = base;
