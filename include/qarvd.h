@@ -14,7 +14,7 @@
  *   - Every pointer is DEVICE memory unless its comment says "host".  The caller owns every
  *     buffer; the library allocates nothing.  The only state it keeps between calls is what it
  *     has learnt about a device (its compute-unit count, which kernels already had their LDS
- *     limit raised).
+ *     limit raised) and, for qarvd_quantize_weight_static alone, one fixed device array.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *   - W is fp32 [N,K] row-major: N = d_out rows, K = d_in input channels.  X is [M,K] row-major
  *     (tokens x channels).  Y is [M,N] row-major.  Leading dimensions are in ELEMENTS.
@@ -127,6 +127,24 @@ qarvd_status qarvd_quantize_weight(const float *W, int32_t N, int32_t K, int64_t
                                    float *s_normal, float *s_outlier, int32_t *perm,
                                    int32_t *K_o_host, float *v_out, void *workspace,
                                    size_t workspace_bytes, void *stream);
+
+/*
+ * qarvd_quantize_weight for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture set-up, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments minus the workspace, same results bit for bit.  The detector's workspace lives in a fixed
+ * device array inside the library (528 KB on every GPU the library is used on, held until the
+ * process ends), which limits K to qarvd_quantize_weight_static_max_k() = 16384: a larger K returns
+ * QARVD_ERR_WORKSPACE before anything is launched.  The call allocates nothing (no hipMalloc/hipFree,
+ * no allocating library routine).  All calls on one GPU share that array: two calls that overlap on
+ * the same GPU (different streams or threads) race and give undefined results; calls on one stream,
+ * or separated by a synchronisation, are safe, and nothing of an earlier call is ever read.
+ * Synchronises `stream` before returning, like qarvd_quantize_weight.
+ */
+int32_t qarvd_quantize_weight_static_max_k(void);
+qarvd_status qarvd_quantize_weight_static(const float *W, int32_t N, int32_t K, int64_t ldw,
+                                          const qarvd_detect_cfg *cfg, int8_t *Wq, int64_t ldwq,
+                                          float *s_normal, float *s_outlier, int32_t *perm,
+                                          int32_t *K_o_host, float *v_out, void *stream);
 
 /*
  * ONLINE activation quantization (appendix, kernel (i) plus the online permutation; Sec. 2.2

@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     quant_act,
     quant_act_static,
     quantize_weight,
+    quantize_weight_static,
+    quantize_weight_static_max_k,
     quantize_weight_workspace,
     w8a8_dual_gemm,
     w8a8_dual_gemm_q8,

@@ -60,6 +60,11 @@ def load_library():
     lib.qarvd_quantize_weight.argtypes = [vp, i32, i32, i64, C.POINTER(_DetectCfg), vp, i64, vp, vp, vp,
                                           C.POINTER(i32), vp, vp, C.c_size_t, vp]
     lib.qarvd_quantize_weight.restype = C.c_int
+    lib.qarvd_quantize_weight_static.argtypes = [vp, i32, i32, i64, C.POINTER(_DetectCfg), vp, i64, vp, vp, vp,
+                                                 C.POINTER(i32), vp, vp]
+    lib.qarvd_quantize_weight_static.restype = C.c_int
+    lib.qarvd_quantize_weight_static_max_k.argtypes = []
+    lib.qarvd_quantize_weight_static_max_k.restype = i32
     lib.qarvd_quant_act.argtypes = [vp, C.c_int, i32, i32, i64, vp, i32, vp, i64, vp, vp]
     lib.qarvd_quant_act.restype = C.c_int
     lib.qarvd_quant_act_static.argtypes = [vp, C.c_int, i32, i32, i64, vp, i32, f32, vp, i64, vp]
@@ -227,6 +232,30 @@ def quantize_weight(W: torch.Tensor, tau: float = 3.5, alpha: float = 1.2, align
     _check(st, "qarvd_quantize_weight" if bits == 8 else "qarvd_quantize_weight_w4")
     del keep
     return DualScaleWeight(Wq, sn, so, perm, int(ko.value), N, K, v, bits)
+
+
+def quantize_weight_static_max_k() -> int:
+    return int(load_library().qarvd_quantize_weight_static_max_k())
+
+
+def quantize_weight_static(W: torch.Tensor, out: DualScaleWeight, tau: float = 3.5, alpha: float = 1.2,
+                           align: int = 32, stream=None) -> DualScaleWeight:
+    """qarvd_quantize_weight_static: the offline step into the caller's buffers (`out`: Wq, s_normal,
+    s_outlier, perm and optionally v, already allocated) with the library's fixed device array as the
+    workspace; nothing is allocated by this call.  Sets out.K_o and returns `out`."""
+    lib = load_library()
+    _dev2d(W, "W")
+    if W.dtype != torch.float32:
+        raise TypeError("W must be float32")
+    N, K = W.shape
+    cfg = _DetectCfg(float(tau), float(alpha), int(align), 0, None)
+    ko = C.c_int32(-1)
+    st = lib.qarvd_quantize_weight_static(_ptr(W), N, K, W.stride(0), C.byref(cfg), _ptr(out.Wq), out.Wq.stride(0),
+                                          _ptr(out.s_normal), _ptr(out.s_outlier), _ptr(out.perm), C.byref(ko),
+                                          _ptr(out.v), _stream(stream))
+    _check(st, "qarvd_quantize_weight_static")
+    out.K_o, out.N, out.K = int(ko.value), N, K
+    return out
 
 
 def quant_act(X: torch.Tensor, perm: Optional[torch.Tensor], K_o: int, Xq: Optional[torch.Tensor] = None,

@@ -474,6 +474,52 @@ extern "C" qarvd_status qarvd_quantize_weight(const float *W, int32_t N, int32_t
                                 workspace_bytes, stream);
 }
 
+// ---- the same offline step for callers that cannot allocate ----------------------------------------------
+// The detector's workspace (norms, ranks, sorted copies, deviations, selection flags, the scalars) lives in a
+// file-scope device array instead of a caller buffer: 528 KB per GPU the library runs on, held until the
+// process ends.  In host code the array's name is only a stand-in; its device address is looked up once per
+// device with hipGetSymbolAddress and that pointer is what the kernels get.
+namespace {
+constexpr int32_t STATIC_SCRATCH_MAX_K = 16384;
+// carve() for K = 16384: 256 (scalars) + 4 x 65536 (v, sorted v, rank, pos) + 2 x 131072 (d, sorted d) + 16384 (flags)
+constexpr size_t STATIC_SCRATCH_BYTES = 256 + 4 * 65536 + 2 * 131072 + 16384;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+// device address of `scratch` on the current device (each GPU holds its own copy at its own address)
+qarvd_status static_scratch_ptr(void **out)
+{
+    static void *ptr[64] = {nullptr};
+    int dev = 0;
+    QARVD_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return QARVD_ERR_UNSUPPORTED;
+    void *p = __atomic_load_n(&ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        QARVD_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return QARVD_ERR_HIP;
+        __atomic_store_n(&ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return QARVD_OK;
+}
+}  // namespace
+
+extern "C" int32_t qarvd_quantize_weight_static_max_k(void) { return STATIC_SCRATCH_MAX_K; }
+
+extern "C" qarvd_status qarvd_quantize_weight_static(const float *W, int32_t N, int32_t K, int64_t ldw,
+                                                     const qarvd_detect_cfg *cfg, int8_t *Wq, int64_t ldwq,
+                                                     float *s_normal, float *s_outlier, int32_t *perm,
+                                                     int32_t *K_o_host, float *v_out, void *stream)
+{
+    if (K > STATIC_SCRATCH_MAX_K) return QARVD_ERR_WORKSPACE;      // the fixed array holds the workspace of K <= 16384
+    if (K > 0 && carve(nullptr, K, nullptr) > STATIC_SCRATCH_BYTES) return QARVD_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (qarvd_status st = static_scratch_ptr(&ws); st != QARVD_OK) return st;
+    // Every kernel of the step writes the part of the workspace it owns before anything reads it (the existing
+    // entry point is given uninitialised memory too), so what an earlier call left behind is never read.
+    return quantize_weight_impl(8, W, N, K, ldw, cfg, Wq, ldwq, s_normal, s_outlier, perm, K_o_host, v_out, ws,
+                                STATIC_SCRATCH_BYTES, stream);
+}
+
 extern "C" size_t qarvd_quantize_weight_w4_workspace(int32_t N, int32_t K)
 {
     if (N <= 0 || K <= 0 || K > QARVD_MAX_K) return 0;
