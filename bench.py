@@ -84,7 +84,7 @@ def main():
         X = torch.from_numpy(L["X"]).to(dev)
         layer = dict(spec=s, w=w, X=X, bias=torch.from_numpy(L["bias"]).to(dev),
                      perm=w.perm if w.K_o > 0 else None,
-                     Xq=torch.empty((s.M, q.packed_k(s.K, w.K_o)), dtype=torch.int8, device=dev),
+                     Xq=torch.empty((s.M, q.packed_ld(s.K, w.K_o)), dtype=torch.int8, device=dev),
                      sx=torch.empty(s.M, dtype=torch.float32, device=dev),
                      Y=torch.empty((s.M, s.N), dtype=torch.bfloat16, device=dev))
         if not args.no_bf16:

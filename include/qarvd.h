@@ -95,6 +95,17 @@ int32_t qarvd_packed_normal_offset(int32_t K_o);
  */
 int32_t qarvd_packed_k(int32_t K, int32_t K_o);
 
+/*
+ * Recommended row stride in bytes for the packed INT8 operands (ldxq, ldwq) of a K-channel layer: the
+ * packed extent qarvd_packed_k(K, K_o) plus 128 (plus 256 where that would be a multiple of 512).  Every
+ * multiple of 16 that is >= the packed extent is
+ * accepted; this one keeps all rows 128-byte aligned (a 64-byte stage segment never straddles a cache
+ * line) and is never a multiple of 512, so the rows of an operand tile spread over the memory channels
+ * (measured on MI355X: GEMMs run 4-16 % slower at row strides of 1536, 5120 or 13824 bytes).  The
+ * bytes between the packed extent and the stride are neither read nor written.  Returns 0 on bad arguments.
+ */
+int32_t qarvd_packed_ld(int32_t K, int32_t K_o);
+
 /* Bytes of device workspace qarvd_quantize_weight needs for an [N,K] layer. */
 size_t qarvd_quantize_weight_workspace(int32_t N, int32_t K);
 

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     load_library,
     packed_channel_map,
     packed_k,
+    packed_ld,
     packed_normal_offset,
     probe_mfma_peak,
     q8_gemm_num_variants,

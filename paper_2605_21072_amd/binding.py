@@ -55,6 +55,8 @@ def load_library():
     lib.qarvd_packed_normal_offset.restype = i32
     lib.qarvd_packed_k.argtypes = [i32, i32]
     lib.qarvd_packed_k.restype = i32
+    lib.qarvd_packed_ld.argtypes = [i32, i32]
+    lib.qarvd_packed_ld.restype = i32
     lib.qarvd_quantize_weight_workspace.argtypes = [i32, i32]
     lib.qarvd_quantize_weight_workspace.restype = C.c_size_t
     lib.qarvd_quantize_weight.argtypes = [vp, i32, i32, i64, C.POINTER(_DetectCfg), vp, i64, vp, vp, vp,
@@ -133,6 +135,11 @@ def packed_k(K: int, K_o: int = -1) -> int:
     return int(load_library().qarvd_packed_k(K, K_o))
 
 
+def packed_ld(K: int, K_o: int = -1) -> int:
+    """qarvd_packed_ld: the recommended row stride of packed INT8 operands (packed extent + 128 bytes)."""
+    return int(load_library().qarvd_packed_ld(K, K_o))
+
+
 def quantize_weight_workspace(N: int, K: int) -> int:
     return int(load_library().qarvd_quantize_weight_workspace(N, K))
 
@@ -206,7 +213,7 @@ def quantize_weight(W: torch.Tensor, tau: float = 3.5, alpha: float = 1.2, align
     if bits not in (4, 8):
         raise ValueError("bits must be 4 or 8")
     if ldwq is None:
-        ldwq = packed_k(K, -1) if (forced_mask is not None or align % 32) else (K + 127) // 128 * 128
+        ldwq = packed_ld(K, -1) if (forced_mask is not None or align % 32) else (K + 127) // 128 * 128 + 128
         if bits == 4:
             ldwq //= 2
     Wq = torch.empty((N, ldwq), dtype=torch.int8 if bits == 8 else torch.uint8, device=dev)
@@ -265,7 +272,7 @@ def quant_act(X: torch.Tensor, perm: Optional[torch.Tensor], K_o: int, Xq: Optio
     _dev2d(X, "X")
     M, K = X.shape
     if Xq is None:
-        Xq = torch.empty((M, packed_k(K, K_o)), dtype=torch.int8, device=X.device)
+        Xq = torch.empty((M, packed_ld(K, K_o)), dtype=torch.int8, device=X.device)   # row stride: see qarvd_packed_ld
     if s_x is None:
         s_x = torch.empty(M, dtype=torch.float32, device=X.device)
     st = lib.qarvd_quant_act(_ptr(X), _dt(X), M, K, X.stride(0), _ptr(perm), K_o, _ptr(Xq), Xq.stride(0), _ptr(s_x),
@@ -281,7 +288,7 @@ def quant_act_static(X: torch.Tensor, perm: Optional[torch.Tensor], K_o: int, sc
     _dev2d(X, "X")
     M, K = X.shape
     if Xq is None:
-        Xq = torch.empty((M, packed_k(K, K_o)), dtype=torch.int8, device=X.device)
+        Xq = torch.empty((M, packed_ld(K, K_o)), dtype=torch.int8, device=X.device)
     st = lib.qarvd_quant_act_static(_ptr(X), _dt(X), M, K, X.stride(0), _ptr(perm), K_o, C.c_float(scale), _ptr(Xq),
                                     Xq.stride(0), _stream(stream))
     _check(st, "qarvd_quant_act_static")

@@ -10,7 +10,7 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libqarvd.so"
-SOURCES = ["quant_act.hip", "quantize_weight.hip", "gemm_api.hip", "gemm_staged.hip", "gemm_dma.hip", "gemm_mfma16.hip", "probe.hip"]
+SOURCES = ["quant_act.hip", "quantize_weight.hip", "gemm_api.hip", "gemm_staged.hip", "gemm_dma.hip", "gemm_dma128.hip", "gemm_mfma16.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # QARVD_PROF=1 in the environment compiles the GEMM kernels with their per-wave tick counters
 FLAGS = (["-DQARVD_PROF=" + os.environ["QARVD_PROF"]] if os.environ.get("QARVD_PROF") else []) + [

@@ -29,6 +29,16 @@ const Variant kVariants[] = {
     {"lds-direct 64x128 (4 waves, 5 stages) single", 64, 128, 0, true, launch_dma<64, 128, 2, 2, 5, false>},
     {"lds-direct 64x64 (4 waves, 6 stages) dual", 64, 64, 128, true, launch_dma<64, 64, 2, 2, 6, true>},
     {"lds-direct 64x64 (4 waves, 6 stages) single", 64, 64, 0, true, launch_dma<64, 64, 2, 2, 6, false>},
+    {"lds-direct 256x128 (8 waves, 6 stages) dual", 256, 128, 128, true, launch_dma<256, 128, 4, 2, 6, true>},
+    {"lds-direct 256x128 (8 waves, 6 stages) single", 256, 128, 0, true, launch_dma<256, 128, 4, 2, 6, false>},
+    {"lds-direct 256x128 (8 waves, 5 stages) dual", 256, 128, 128, true, launch_dma<256, 128, 4, 2, 5, true>},
+    {"lds-direct 256x128 (8 waves, 5 stages) single", 256, 128, 0, true, launch_dma<256, 128, 4, 2, 5, false>},
+    {"128-byte stages 256x256 (8 waves, 2 stages) dual", 256, 256, 128, true, launch_dma128<256, 256, 2, 4, 2, true>},
+    {"128-byte stages 256x256 (8 waves, 2 stages) single", 256, 256, 0, true, launch_dma128<256, 256, 2, 4, 2, false>},
+    {"128-byte stages 256x128 (8 waves, 3 stages) dual", 256, 128, 128, true, launch_dma128<256, 128, 4, 2, 3, true>},
+    {"128-byte stages 256x128 (8 waves, 3 stages) single", 256, 128, 0, true, launch_dma128<256, 128, 4, 2, 3, false>},
+    {"128-byte stages 128x256 (8 waves, 3 stages) dual", 128, 256, 128, true, launch_dma128<128, 256, 2, 4, 3, true>},
+    {"128-byte stages 128x256 (8 waves, 3 stages) single", 128, 256, 0, true, launch_dma128<128, 256, 2, 4, 3, false>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 

@@ -90,6 +90,8 @@ template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool W4 = false
 qarvd_status launch_dma(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>   // INT8 output quantized in the epilogue
 qarvd_status launch_dma_q8(const GemmArgs &g, hipStream_t st);
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>   // 128-byte-deep K stages (gemm_dma128.hip)
+qarvd_status launch_dma128(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
 qarvd_status launch_mfma16(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 

@@ -379,8 +379,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
         load_frags(sb, 1);
         if (use0) mma_r(0);
         if (it + 1 < T) {
-            if (AHEAD >= 3 && T - 2 - it >= 1) wait_vmcnt<G::NLOAD>();
-            else wait_vmcnt<0>();
+            wait_stages_in_flight<(AHEAD >= 2 ? AHEAD - 2 : 0), G::NLOAD>(T - 2 - it);   // stage it + 1 has landed
             __builtin_amdgcn_s_barrier();
             load_frags(smem + nstage * STG, 0);
         }
@@ -661,6 +660,8 @@ QARVD_INST_Q8(128, 128, 2, 2, 4)
 QARVD_INST(256, 256, 2, 4, 4)
 QARVD_INST(256, 128, 4, 2, 4)
 QARVD_INST(128, 256, 2, 4, 4)
+QARVD_INST(256, 128, 4, 2, 6)
+QARVD_INST(256, 128, 4, 2, 5)
 QARVD_INST(256, 128, 2, 2, 3)
 QARVD_INST(192, 128, 2, 2, 3)
 QARVD_INST(128, 128, 2, 2, 4)

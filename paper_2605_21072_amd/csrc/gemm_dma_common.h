@@ -29,6 +29,16 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
+// Waits until at most min(stages, MAXS) stages of NLOAD loads each are still in flight (`stages` is wave-uniform).
+template <int MAXS, int NLOAD> __device__ __forceinline__ void wait_stages_in_flight(int stages)
+{
+    if constexpr (MAXS > 0) {
+        if (stages >= MAXS) wait_vmcnt<MAXS * NLOAD>();
+        else wait_stages_in_flight<MAXS - 1, NLOAD>(stages);
+    } else {
+        wait_vmcnt<0>();
+    }
+}
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14)); }
 
 // One LDS-direct load: lane l moves the 16 bytes at base + voffset(l) + soffset to lds + 16*l (lds and

@@ -383,6 +383,14 @@ extern "C" int32_t qarvd_packed_k(int32_t K, int32_t K_o)
     return qarvd_round_up(K + 31, 128);
 }
 
+extern "C" int32_t qarvd_packed_ld(int32_t K, int32_t K_o)
+{
+    const int32_t kp = qarvd_packed_k(K, K_o);
+    if (kp <= 0) return 0;
+    const int32_t ld = kp + 128;                  // multiples of 128, skipping the multiples of 512
+    return (ld % 512) == 0 ? ld + 128 : ld;
+}
+
 extern "C" size_t qarvd_quantize_weight_workspace(int32_t N, int32_t K)
 {
     if (N <= 0 || K <= 0 || K > QARVD_MAX_K) return 0;

@@ -38,6 +38,11 @@ def test_packed_geometry(lib):
     assert q.packed_k(130, 7) == 256            # 32 + 123 -> 155 -> 256
     assert q.packed_k(96, 96) == 128
     assert q.packed_k(1536, -1) == 1664
+    assert q.packed_ld(1536, 32) == 1664 and q.packed_ld(8960, 0) == 9088 and q.packed_ld(0, 0) == 0
+    for K in (96, 384, 1536, 5120, 13824, 20000):
+        for ko in (0, 32, -1):
+            ld = q.packed_ld(K, ko)
+            assert ld % 128 == 0 and ld % 512 != 0 and 128 <= ld - q.packed_k(K, ko) <= 256
     assert q.packed_k(0, 0) == 0 and q.packed_k(10, 11) == 0 and q.packed_k(133144, 0) == 0
     for K in (1, 37, 128, 1000, 1536):
         worst = max(q.packed_k(K, ko) for ko in range(0, K + 1))
