@@ -23,6 +23,12 @@ def _outputs(N, K):
                              torch.empty(K, dtype=torch.float32, device="cuda"))
 
 
+def _allocations():
+    """How many device allocations torch's allocator has served so far (frees, e.g. of an earlier test's garbage
+    collected in between, do not change it)."""
+    return torch.cuda.memory_stats().get("allocation.all.allocated", 0)
+
+
 def _same(a, b):
     assert a.K_o == b.K_o
     kp = q.packed_k(a.K, a.K_o)
@@ -44,9 +50,9 @@ def test_static_scratch_entry_point_matches_the_workspace_one_twice_in_a_row():
         N, K = W.shape
         ref = q.quantize_weight(W)                    # the existing entry point (caller-provided workspace)
         out = _outputs(N, K)                          # the caller's buffers
-        before = torch.cuda.memory_allocated()
+        before = _allocations()
         q.quantize_weight_static(W, out)              # fills `out` in place
-        assert torch.cuda.memory_allocated() == before           # nothing of torch's was allocated by the call either
+        assert _allocations() == before               # nothing of torch's was allocated by the call either
         torch.cuda.synchronize()
         _same(out, ref)
         assert out.K_o == (L["spec"].n_outlier + 31) // 32 * 32
