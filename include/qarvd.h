@@ -225,9 +225,11 @@ qarvd_status qarvd_quantize_weight_w4(const float *W, int32_t N, int32_t K, int6
  * which the scales undo exactly), so both INT32 sums and every output are those of the INT8 path on
  * the same codes.
  *   Wq4  in  packed u8 [N, ldwq4] for the same (K, K_o) as Xq; 16-byte aligned, ldwq4 % 16 == 0
- * Needs the fast-path preconditions (N % 8 == 0, 16-byte aligned Y rows, scales and bias, outlier
- * block of at most 128 packed bytes); otherwise returns QARVD_ERR_UNSUPPORTED.  variant: 0 = heuristic,
- * 1..qarvd_w4_gemm_num_variants() pick a kernel.  Fully asynchronous on `stream`.
+ * Shapes outside the fast-path preconditions (N % 8 != 0, Y rows, scales or bias not 16-byte aligned,
+ * an outlier block of more than 128 packed bytes) run on a slower register-staged kernel (the last
+ * variant); asking for one of the fast variants by number on such a shape returns
+ * QARVD_ERR_UNSUPPORTED.  variant: 0 = heuristic, 1..qarvd_w4_gemm_num_variants() pick a kernel.
+ * Fully asynchronous on `stream`.
  */
 qarvd_status qarvd_w4a8_dual_gemm(const int8_t *Xq, int64_t ldxq, const float *s_x,
                                   const uint8_t *Wq4, int64_t ldwq4, const float *s_normal,

@@ -57,19 +57,17 @@ bool variant_fits(const Variant &v, const GemmArgs &g, qarvd_dtype ydt)
     return true;
 }
 
-// Heuristic: a three-constant cost model per LDS-direct variant, fitted to timings on MI355X over the
-// DiT shapes (M = 520..4680, N and K in {1536, 5120, 8960, 13824}):
-//     time ~ c + ceil(tiles / CUs) * (a + b * T),     T = packed K / 64   (constants in us, fitted on MI355X)
-// c is launch plus the first tile's lead-in, a a tile's epilogue and hand-over, b one K iteration of a
-// tile that has its CU to itself (two four-wave workgroups sharing a CU each run at half speed, which
-// the ceil over 256 CUs already accounts for).  The 256x256 tile has the cheapest iteration per MAC and
-// wins when N is wide; the 128x256 eight-wave tile fills the chip when N = 1536; the 128x128 tile wins
-// for short M, and the 64x64 / 64x128 tiles when even those would leave most CUs without a tile (M of a few
-// hundred rows with N = 1536: 24 us instead of 37 us at K = 8960); the 16x16x64 kernel overtakes the
-// 256x256 one once K is long enough to amortise its dearer epilogue.  The constants of the two eight-wave
-// half tiles come from timings inside a sequence of layers, where the activations have just been written and
-// the weights come from memory: there the tall 256x128 tile (each weight panel fetched by half as many tiles)
-// beats the wide 128x256 one by 9 %, although launched back to back on cached operands it is 2 % slower.
+// Heuristic: a three-constant cost model per candidate, fitted to back-to-back timings on MI355X over the
+// DiT shapes (M = 256..4680, N and K in {1536, 4608, 5120, 8960, 13824}, operands at the padded strides of
+// qarvd_packed_ld):
+//     time ~ c + ceil(tiles / CUs) * (a + b * T),     T = packed K / 64          (constants in microseconds)
+// c is launch plus the first tile's lead-in, a a tile's epilogue and hand-over, b one 64-byte K step of a tile
+// that has its CU to itself (two four-wave workgroups sharing a CU each run at half speed, which the ceil over
+// the CUs already accounts for).  The three eight-wave tiles run on 128-byte-deep stages (gemm_dma128.hip):
+// 256x256 has the cheapest K step per MAC and wins when N is wide; the half tiles fill the chip when N = 1536
+// (4680 x 8960 -> 1536: 61 us against 81 us for 256x256) and on M of a few hundred rows with N = 8960.  The
+// four-wave tiles on 64-byte stages serve short M: 128x128 for M around 1500, 64x128 / 64x64 when even those
+// would leave most CUs without a tile (M = 520, N = 1536, K = 8960: 24 us instead of 45 us).
 int device_cus()
 {
     int cus = 0;
@@ -82,10 +80,9 @@ int pick_variant(const GemmArgs &g, qarvd_dtype ydt)
     const int cus = device_cus();      // rounds are counted over the CUs of the device the call runs on
     if (g.n_off <= 128 && vector_out_ok(g, ydt)) {
         struct Cand { int variant, bm, bn; double c, a, b; };
-        const Cand cand[7] = {{dual ? 11 : 12, 256, 256, 2.2, 8.9, 0.688},
-                              {dual ? 17 : 18, 256, 224, 4.0, 11.5, 0.621},
-                              {dual ? 15 : 16, 128, 256, 5.0, 2.75, 0.550},
-                              {dual ? 13 : 14, 256, 128, 4.5, 2.0, 0.505},
+        const Cand cand[6] = {{dual ? 27 : 28, 256, 256, 7.2, 9.2, 0.443},
+                              {dual ? 29 : 30, 256, 128, 4.5, 3.6, 0.379},
+                              {dual ? 31 : 32, 128, 256, 3.9, 3.9, 0.381},
                               {dual ? 9 : 10, 128, 128, 2.0, 1.5, 0.309},
                               {dual ? 19 : 20, 64, 128, 2.0, 0.8, 0.187},
                               {dual ? 21 : 22, 64, 64, 2.0, 0.77, 0.152}};
@@ -144,7 +141,7 @@ extern "C" qarvd_status qarvd_w8a8_dual_gemm_variant(int32_t variant, const int8
     g.Xq = Xq; g.Wq = Wq; g.s_x = s_x; g.s_n = s_normal; g.s_o = s_outlier; g.bias = bias;
     g.Y = Y; g.dbg_n = dbg_acc_normal; g.dbg_o = dbg_acc_outlier;
     g.ldxq = ldxq; g.ldwq = ldwq; g.ldy = ldy; g.M = M; g.N = N; g.n_off = pk.n_off; g.kp = pk.kp;
-    g.tiles_m = g.tiles_n = 0; g.act = 0; g.out_scale = 0.0f;
+    g.tiles_m = g.tiles_n = 0; g.act = 0; g.out_scale = 0.0f; g.store_wt = 0;
     if (variant == 0) variant = pick_variant(g, ydt);
     const Variant &v = kVariants[variant - 1];
     if (!variant_fits(v, g, ydt)) return QARVD_ERR_UNSUPPORTED;
@@ -172,6 +169,8 @@ struct W4Variant {
 const W4Variant kW4Variants[] = {
     {256, 256, launch_dma<256, 256, 2, 4, 4, true, true>, launch_dma<256, 256, 2, 4, 4, false, true>},
     {128, 128, launch_dma<128, 128, 2, 2, 4, true, true>, launch_dma<128, 128, 2, 2, 4, false, true>},
+    // register-staged: any N, any outlier-block width, any output alignment
+    {128, 128, launch_staged<128, 128, 2, 2, true, true>, launch_staged<128, 128, 2, 2, false, true>},
 };
 constexpr int kNumW4Variants = sizeof(kW4Variants) / sizeof(kW4Variants[0]);
 }  // namespace
@@ -201,8 +200,12 @@ extern "C" qarvd_status qarvd_w4a8_dual_gemm(const int8_t *Xq, int64_t ldxq, con
     g.Xq = Xq; g.Wq = reinterpret_cast<const int8_t *>(Wq4); g.s_x = s_x; g.s_n = s_normal; g.s_o = s_outlier; g.bias = bias;
     g.Y = Y; g.dbg_n = dbg_acc_normal; g.dbg_o = dbg_acc_outlier;
     g.ldxq = ldxq; g.ldwq = ldwq4; g.ldy = ldy; g.M = M; g.N = N; g.n_off = pk.n_off; g.kp = pk.kp;
-    g.tiles_m = g.tiles_n = 0; g.act = 0; g.out_scale = 0.0f;
-    if (g.n_off > 128 || !vector_out_ok(g, ydt)) return QARVD_ERR_UNSUPPORTED;
+    g.tiles_m = g.tiles_n = 0; g.act = 0; g.out_scale = 0.0f; g.store_wt = 0;
+    const bool fast_ok = g.n_off <= 128 && vector_out_ok(g, ydt);
+    if (!fast_ok) {
+        if (variant == 1 || variant == 2) return QARVD_ERR_UNSUPPORTED;     // an LDS-direct tile asked for by name
+        variant = kNumW4Variants;                                           // the register-staged kernel takes the rest
+    }
     if (variant == 0) {     // same cost model as the INT8 path, restricted to the two tiles built for INT4
         const double T = g.kp / 64;
         const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256), t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
@@ -227,6 +230,9 @@ const Q8Variant kQ8Variants[] = {
     {256, 256, 2.2, 8.9, 0.688, launch_dma_q8<256, 256, 2, 4, 4, true>, launch_dma_q8<256, 256, 2, 4, 4, false>},
     {128, 256, 5.0, 2.75, 0.490, launch_dma_q8<128, 256, 2, 4, 4, true>, launch_dma_q8<128, 256, 2, 4, 4, false>},
     {128, 128, 2.0, 1.5, 0.309, launch_dma_q8<128, 128, 2, 2, 4, true>, launch_dma_q8<128, 128, 2, 2, 4, false>},
+    {256, 256, 7.2, 9.2, 0.443, launch_dma128_q8<256, 256, 2, 4, 2, true>, launch_dma128_q8<256, 256, 2, 4, 2, false>},
+    {256, 128, 4.5, 3.6, 0.379, launch_dma128_q8<256, 128, 4, 2, 3, true>, launch_dma128_q8<256, 128, 4, 2, 3, false>},
+    {128, 256, 3.9, 3.9, 0.381, launch_dma128_q8<128, 256, 2, 4, 3, true>, launch_dma128_q8<128, 256, 2, 4, 3, false>},
 };
 constexpr int kNumQ8Variants = sizeof(kQ8Variants) / sizeof(kQ8Variants[0]);
 }  // namespace
@@ -257,7 +263,7 @@ extern "C" qarvd_status qarvd_w8a8_dual_gemm_q8(const int8_t *Xq, int64_t ldxq, 
     g.Xq = Xq; g.Wq = Wq; g.s_x = s_x; g.s_n = s_normal; g.s_o = s_outlier; g.bias = bias;
     g.Y = Y8; g.dbg_n = nullptr; g.dbg_o = nullptr;
     g.ldxq = ldxq; g.ldwq = ldwq; g.ldy = ldy8; g.M = M; g.N = N; g.n_off = pk.n_off; g.kp = pk.kp;
-    g.tiles_m = g.tiles_n = 0; g.act = (int32_t)act; g.out_scale = out_scale;
+    g.tiles_m = g.tiles_n = 0; g.act = (int32_t)act; g.out_scale = out_scale; g.store_wt = 0;
     if (g.n_off > 128) return QARVD_ERR_UNSUPPORTED;
     if (variant == 0) {
         const double T = g.kp / 64;

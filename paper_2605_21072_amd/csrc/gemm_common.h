@@ -41,6 +41,7 @@ struct GemmArgs {
     // next layer's static activation scale; unused for fp32 / bf16 outputs
     int32_t act;
     float out_scale;
+    int32_t store_wt;  // output stores write through the L2 (small outputs); set by the launchers
 };
 
 // LDS image of an operand tile: row r at byte r*128, its eight 16-byte chunks XOR-swizzled by
@@ -84,12 +85,14 @@ struct Variant {
 };
 
 // launchers defined in gemm_staged.hip / gemm_dma.hip
-template <int BM, int BN, int WM, int WN, bool DUAL>
+template <int BM, int BN, int WM, int WN, bool DUAL, bool W4 = false>
 qarvd_status launch_staged(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL, bool W4 = false>   // W4: Wq is packed INT4, ldwq in bytes
 qarvd_status launch_dma(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>   // INT8 output quantized in the epilogue
 qarvd_status launch_dma_q8(const GemmArgs &g, hipStream_t st);
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
+qarvd_status launch_dma128_q8(const GemmArgs &g, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>   // 128-byte-deep K stages (gemm_dma128.hip)
 qarvd_status launch_dma128(const GemmArgs &g, qarvd_dtype ydt, hipStream_t st);
 template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>

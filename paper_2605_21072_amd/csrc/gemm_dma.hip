@@ -417,6 +417,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
     const int y_lane = (wm * G::WTM + (lane >> 2)) * ldy_b + (n0 + wn * G::WTN + (lane & 3) * EPC) * ESZ;
     const int n_left = g.N - n0 - wn * G::WTN - (lane & 3) * EPC;     // columns from this lane's chunk to the matrix edge
     const bool has_o = DUAL && o_steps > 0;
+    const bool wt = g.store_wt != 0;
     const float out_rscale = sizeof(OutT) == 1 ? 1.0f / g.out_scale : 0.0f;     // IEEE division: RN(1 / s)
 
     // The epilogue is a chain of LDS round trips (scales in, patch out and back) around little arithmetic,
@@ -453,7 +454,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
                 stored = true;
             }
 #pragma unroll
-            for (int p = 0; p < 2; ++p) buffer_store16(y_tile, y_bytes, pend_voff, pend_soff + p * 16 * ldy_b, pend[p]);
+            for (int p = 0; p < 2; ++p) buffer_store16(y_tile, y_bytes, pend_voff, pend_soff + p * 16 * ldy_b, pend[p], wt);
             pending = false;
         };
         auto flush_issue = [&](int i, int col0) {   // col0: first column of the pass inside the wave tile
@@ -627,6 +628,7 @@ qarvd_status launch_dma(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     GemmArgs g = g0;
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
+    g.store_wt = store_write_through(g, ydt == QARVD_BF16 ? 2 : 4);
     const bool dbg = g.dbg_n != nullptr || g.dbg_o != nullptr;   // raw-accumulator dumps: separate, slower build
     if (ydt == QARVD_BF16)
         return !dbg ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, uint16_t, W4>(g, st)
@@ -641,6 +643,7 @@ qarvd_status launch_dma_q8(const GemmArgs &g0, hipStream_t st)
     GemmArgs g = g0;
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
+    g.store_wt = store_write_through(g, 1);
     return launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, int8_t, false>(g, st);
 }
 

@@ -353,6 +353,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
     const int y_lane = (wm * G::WTM + (lane >> 2)) * ldy_b + (n0 + wn * G::WTN + (lane & 3) * EPC) * ESZ;
     const int n_left = g.N - n0 - wn * G::WTN - (lane & 3) * EPC;     // columns from this lane's chunk to the matrix edge
     const bool has_o = DUAL && o_steps > 0;
+    const bool wt = g.store_wt != 0;
+    const float out_rscale = sizeof(OutT) == 1 ? 1.0f / g.out_scale : 0.0f;     // IEEE division: RN(1 / s)
 
     // Software pipeline over 32 x 32 blocks, as in the 64-byte-stage kernel: a patch is read back as soon as it
     // is complete and stored after the next block's arithmetic; the outlier MFMAs of the next block start before
@@ -378,7 +380,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
                 stored = true;
             }
 #pragma unroll
-            for (int p = 0; p < 2; ++p) buffer_store16(y_tile, y_bytes, pend_voff, pend_soff + p * 16 * ldy_b, pend[p]);
+            for (int p = 0; p < 2; ++p) buffer_store16(y_tile, y_bytes, pend_voff, pend_soff + p * 16 * ldy_b, pend[p], wt);
             pending = false;
         };
         auto flush_issue = [&](int i, int col0) {   // col0: first column of the pass inside the wave tile
@@ -472,7 +474,14 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
                         }
                     }
                 }
-                if constexpr (sizeof(OutT) == 2) {
+                if constexpr (sizeof(OutT) == 1) {
+                    // chained layer: activation, then the next layer's static scale (Eq. (quantization)); two
+                    // blocks of 32 INT8 columns share a 64-byte patch row
+                    static_assert(sizeof(OutT) != 1 || TN % 2 == 0, "INT8 output pairs the column blocks");
+                    const unsigned pk = quantize4_static(y, g.act == 1, g.out_scale, out_rscale);
+                    const int c = 2 * (j & 1) + (q >> 1);
+                    *reinterpret_cast<unsigned *>(patch + frow * PATCH2_RS + ((c ^ pswz) << 4) + 8 * (q & 1) + 4 * fhalf) = pk;
+                } else if constexpr (sizeof(OutT) == 2) {
                     v2u pk;
                     pk.x = cvt_pk_bf16(y[0], y[1]);
                     pk.y = cvt_pk_bf16(y[2], y[3]);
@@ -484,6 +493,9 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
                 }
             }
             if constexpr (sizeof(OutT) == 2) flush(i, j * 32);
+            if constexpr (sizeof(OutT) == 1) {
+                if (j & 1) flush(i, (j - 1) * 32);
+            }
         }
         flush_commit();
     };
@@ -543,6 +555,7 @@ qarvd_status launch_dma128(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     GemmArgs g = g0;
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
+    g.store_wt = store_write_through(g, ydt == QARVD_BF16 ? 2 : 4);
     const bool dbg = g.dbg_n != nullptr || g.dbg_o != nullptr;   // raw-accumulator dumps: separate, slower build
     if (ydt == QARVD_BF16)
         return !dbg ? launch128_one<BM, BN, WM, WN, NSTAGE, DUAL, false, uint16_t>(g, st)
@@ -550,6 +563,23 @@ qarvd_status launch_dma128(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     return !dbg ? launch128_one<BM, BN, WM, WN, NSTAGE, DUAL, false, float>(g, st)
                 : launch128_one<BM, BN, WM, WN, NSTAGE, DUAL, true, float>(g, st);
 }
+
+template <int BM, int BN, int WM, int WN, int NSTAGE, bool DUAL>
+qarvd_status launch_dma128_q8(const GemmArgs &g0, hipStream_t st)
+{
+    GemmArgs g = g0;
+    g.tiles_m = (g.M + BM - 1) / BM;
+    g.tiles_n = (g.N + BN - 1) / BN;
+    g.store_wt = store_write_through(g, 1);
+    return launch128_one<BM, BN, WM, WN, NSTAGE, DUAL, false, int8_t>(g, st);
+}
+
+#define QARVD_INST128_Q8(BM, BN, WM, WN, NS)                                                         \
+    template qarvd_status launch_dma128_q8<BM, BN, WM, WN, NS, true>(const GemmArgs &, hipStream_t); \
+    template qarvd_status launch_dma128_q8<BM, BN, WM, WN, NS, false>(const GemmArgs &, hipStream_t);
+QARVD_INST128_Q8(256, 256, 2, 4, 2)
+QARVD_INST128_Q8(256, 128, 4, 2, 3)
+QARVD_INST128_Q8(128, 256, 2, 4, 3)
 
 #define QARVD_INST128(BM, BN, WM, WN, NS)                                                                        \
     template qarvd_status launch_dma128<BM, BN, WM, WN, NS, true>(const GemmArgs &, qarvd_dtype, hipStream_t);   \

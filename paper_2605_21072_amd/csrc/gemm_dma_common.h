@@ -7,6 +7,12 @@ namespace qarvd_gemm {
 #ifndef QARVD_PROF
 #define QARVD_PROF 0
 #endif
+#ifndef QARVD_NO_STORE
+#define QARVD_NO_STORE 0                   // diagnostic builds: 1 = output stores dropped by the range check, 2 = not issued
+#endif
+#ifndef QARVD_STORE_AUX
+#define QARVD_STORE_AUX 0                  // cache policy bits of the output stores
+#endif
 constexpr int BKD = 64;                   // K bytes per stage row
 #define QARVD_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define QARVD_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -58,19 +64,27 @@ __device__ __forceinline__ void buffer_load_lds16(const void *base, int voffset,
 // One 16-byte store per lane through a raw buffer descriptor over [base, base + bytes): lanes whose
 // byte offset voffset + soffset falls at or past `bytes` are dropped by the hardware, which is how the
 // output rows below a ragged last tile are masked (checked on MI355X).  base, bytes, soffset wave-uniform.
-__device__ __forceinline__ void buffer_store16(void *base, int bytes, int voffset, int soffset, v4i data)
+// `write_through` (wave-uniform) sends the data on to memory at once instead of leaving dirty lines in the
+// L2: a kernel ends with a write-back of what its XCDs' L2s still hold, which for an output of a few MB is
+// most of it -- 1-2 us at the end of a 17 us GEMM; for outputs much larger than the L2s it only adds traffic
+// while the kernel computes (measured: 4680 x 1536 bf16 18.0 -> 16.2 us, 4680 x 8960 72 -> 75 us).
+__device__ __forceinline__ void buffer_store16(void *base, int bytes, int voffset, int soffset, v4i data, bool write_through = false)
 {
-#if defined(__HIP_DEVICE_COMPILE__)
+#if defined(__HIP_DEVICE_COMPILE__) && QARVD_NO_STORE != 2
     typedef unsigned int v4u_t __attribute__((ext_vector_type(4)));
-    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(base, 0, bytes, 0x00020000);
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u_t, data), r, voffset, soffset, 0);
+    // (diagnostic build QARVD_NO_STORE = 1: an empty range, so every store is issued and then dropped)
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(base, 0, QARVD_NO_STORE == 1 ? 0 : bytes, 0x00020000);
+    if (write_through)
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u_t, data), r, voffset, soffset, 17);   // sc0 sc1
+    else
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u_t, data), r, voffset, soffset, QARVD_STORE_AUX);
     // A 16-byte buffer store still reads its data registers in the cycle after it issues.  The compiler
     // keeps that slot free of VALU writes to them only when the scalar offset is an immediate; with a
     // register offset it let one through, and the first dword of some lanes went out overwritten
     // (seen on MI355X as sporadic wrong outputs).  Hold the registers for two more wait states.
     asm volatile("s_nop 1" : : "v"(data));
 #else
-    (void)base; (void)bytes; (void)voffset; (void)soffset; (void)data;
+    (void)base; (void)bytes; (void)voffset; (void)soffset; (void)data; (void)write_through;
 #endif
 }
 
@@ -159,6 +173,13 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b)
     v2f f = {a, b};
     v2bf h = __builtin_convertvector(f, v2bf);
     return __builtin_bit_cast(uint32_t, h);
+}
+
+// Outputs up to 40 MB are stored write-through (see buffer_store16): 4680 x 1536 and 1560 x 8960 bf16 gain
+// 1-2 us, 4680 x 8960 (84 MB) loses 3.
+inline int32_t store_write_through(const GemmArgs &g, int elem_bytes)
+{
+    return (size_t)g.M * (size_t)g.N * (size_t)elem_bytes <= ((size_t)40 << 20) ? 1 : 0;
 }
 
 // persistent grid size: as many workgroups as the chip holds at once (a multiple of the XCD count,

@@ -318,6 +318,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm16_kernel(GemmArgs g)
         constexpr int NBP = sizeof(OutT) == 2 ? 2 : 1;  // 16-column blocks per patch pass (64 bytes per row)
         const int pswz = (frow >> 2) & 3;
         const bool has_o = DUAL && o32 > 0;
+        const bool wt = g.store_wt != 0;
         // patch -> global: 16 rows x (16 * chunks) bytes in one instruction through a buffer descriptor over
         // the rows of this tile that exist (rows below the matrix are dropped by its range check)
         constexpr int ESZ = (int)sizeof(OutT);
@@ -330,7 +331,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm16_kernel(GemmArgs g)
             const int row = lane >> 2, ch = lane & 3;
             const v4i v = *reinterpret_cast<const v4i *>(patch + row * P16_RS + ((ch ^ ((row >> 2) & 3)) << 4));
             const int voff = (ch < chunks && col0 + EPC <= n_left) ? y_lane : 0x7ffffff0;
-            buffer_store16(y_tile, y_bytes, voff, i * 16 * ldy_b + col0 * ESZ, v);
+            buffer_store16(y_tile, y_bytes, voff, i * 16 * ldy_b + col0 * ESZ, v, wt);
         };
 
         auto epilogue = [&](auto haso_tag) {
@@ -474,6 +475,7 @@ qarvd_status launch_mfma16(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     GemmArgs g = g0;
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
+    g.store_wt = store_write_through(g, ydt == QARVD_BF16 ? 2 : 4);
     const bool dbg = g.dbg_n != nullptr || g.dbg_o != nullptr;   // raw-accumulator dumps: separate, slower build
     if (ydt == QARVD_BF16)
         return !dbg ? launch16_one<BM, BN, WM, WN, NSTAGE, DUAL, false, uint16_t>(g, st)

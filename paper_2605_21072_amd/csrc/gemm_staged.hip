@@ -1,11 +1,15 @@
 // Register-staged variant of the dual-scale W8A8 GEMM: global -> VGPR -> swizzled LDS, two LDS
 // stages of 128 K-bytes, both accumulator sets live in registers.  Handles every shape and any
 // outlier-block width; the general fallback behind the faster LDS-direct kernels.
+// W4: the W operand is packed INT4 (two codes per byte, the nibble order of qarvd_quantize_weight_w4); a thread
+// loads 8 bytes where the INT8 build loads 16 and widens them to sixteen INT8 lanes holding 16 * code on the
+// way into LDS.  Both sums are then 16 times the INT8 ones and the weight scales are multiplied by 1/16 (exact
+// in fp32: a power of two), so every product and fma of the epilogue rounds the same value as the INT8 path.
 #include "gemm_common.h"
 
 namespace qarvd_gemm {
 
-template <int BM, int BN, int WM, int WN, bool DUAL, typename OutT>
+template <int BM, int BN, int WM, int WN, bool DUAL, typename OutT, bool W4>
 __global__ __launch_bounds__(TPB) void gemm_staged_kernel(GemmArgs g)
 {
     static_assert(WM * WN == 4, "four wavefronts");
@@ -30,7 +34,7 @@ __global__ __launch_bounds__(TPB) void gemm_staged_kernel(GemmArgs g)
 #pragma unroll
     for (int i = 0; i < ACH; ++i) pa[i] = g.Xq + (size_t)min(m0 + lrow + 32 * i, g.M - 1) * g.ldxq + lcol * 16;
 #pragma unroll
-    for (int i = 0; i < BCH; ++i) pb[i] = g.Wq + (size_t)min(n0 + lrow + 32 * i, g.N - 1) * g.ldwq + lcol * 16;
+    for (int i = 0; i < BCH; ++i) pb[i] = g.Wq + (size_t)min(n0 + lrow + 32 * i, g.N - 1) * g.ldwq + lcol * (W4 ? 8 : 16);
     const int st_off = lrow * BK + ((lcol ^ swz(lrow)) << 4);   // + i*32*BK; swz(lrow + 32 i) == swz(lrow)
 
     v4i ra[ACH], rb[BCH];
@@ -38,7 +42,15 @@ __global__ __launch_bounds__(TPB) void gemm_staged_kernel(GemmArgs g)
 #pragma unroll
         for (int i = 0; i < ACH; ++i) ra[i] = *reinterpret_cast<const v4i *>(pa[i] + (size_t)kt * BK);
 #pragma unroll
-        for (int i = 0; i < BCH; ++i) rb[i] = *reinterpret_cast<const v4i *>(pb[i] + (size_t)kt * BK);
+        for (int i = 0; i < BCH; ++i) {
+            if constexpr (W4) {
+                const v2i p = *reinterpret_cast<const v2i *>(pb[i] + (size_t)kt * (BK / 2));
+                const int m = (int)0xF0F0F0F0u;
+                rb[i] = v4i{(p.x << 4) & m, p.x & m, (p.y << 4) & m, p.y & m};
+            } else {
+                rb[i] = *reinterpret_cast<const v4i *>(pb[i] + (size_t)kt * BK);
+            }
+        }
     };
     auto sstore = [&](int s) {
         unsigned char *A = smem + s * STAGE, *B = A + BM * BK;
@@ -124,7 +136,8 @@ __global__ __launch_bounds__(TPB) void gemm_staged_kernel(GemmArgs g)
     for (int j = 0; j < TN; ++j) {
         const int n = n0 + wn * (BN / WN) + j * 32 + frow;
         const int nc = min(n, g.N - 1);
-        const float sn = g.s_n[nc], so = g.s_o[nc];
+        const float wsc = W4 ? 0.0625f : 1.0f;
+        const float sn = g.s_n[nc] * wsc, so = g.s_o[nc] * wsc;
         const float bs = g.bias ? g.bias[nc] : 0.0f;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -140,15 +153,15 @@ __global__ __launch_bounds__(TPB) void gemm_staged_kernel(GemmArgs g)
                 v = fmaf(v, sx_lds[ml], bs);
                 if (m < g.M && n < g.N) {
                     store_out<OutT>(Y + (size_t)m * g.ldy + n, v);
-                    if (g.dbg_n) g.dbg_n[(size_t)m * g.N + n] = an;
-                    if (g.dbg_o) g.dbg_o[(size_t)m * g.N + n] = ao;
+                    if (g.dbg_n) g.dbg_n[(size_t)m * g.N + n] = an >> (W4 ? 4 : 0);     // exact multiples of 16
+                    if (g.dbg_o) g.dbg_o[(size_t)m * g.N + n] = ao >> (W4 ? 4 : 0);
                 }
             }
         }
     }
 }
 
-template <int BM, int BN, int WM, int WN, bool DUAL>
+template <int BM, int BN, int WM, int WN, bool DUAL, bool W4>
 qarvd_status launch_staged(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
 {
     GemmArgs g = g0;
@@ -157,12 +170,12 @@ qarvd_status launch_staged(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
     const size_t lds = 2 * (size_t)(BM + BN) * BK + BM * sizeof(float);
     const int grid = g.tiles_m * g.tiles_n;
     if (ydt == QARVD_BF16) {
-        auto k = gemm_staged_kernel<BM, BN, WM, WN, DUAL, uint16_t>;
+        auto k = gemm_staged_kernel<BM, BN, WM, WN, DUAL, uint16_t, W4>;
         static unsigned long long raised = 0;
         if (qarvd_status s_a = qarvd_raise_lds_limit_once(k, (int)lds, raised); s_a != QARVD_OK) return s_a;
         hipLaunchKernelGGL(k, dim3(grid), dim3(TPB), lds, st, g);
     } else {
-        auto k = gemm_staged_kernel<BM, BN, WM, WN, DUAL, float>;
+        auto k = gemm_staged_kernel<BM, BN, WM, WN, DUAL, float, W4>;
         static unsigned long long raised = 0;
         if (qarvd_status s_a = qarvd_raise_lds_limit_once(k, (int)lds, raised); s_a != QARVD_OK) return s_a;
         hipLaunchKernelGGL(k, dim3(grid), dim3(TPB), lds, st, g);
@@ -171,9 +184,11 @@ qarvd_status launch_staged(const GemmArgs &g0, qarvd_dtype ydt, hipStream_t st)
 }
 
 
-template qarvd_status launch_staged<256, 128, 2, 2, true>(const GemmArgs &, qarvd_dtype, hipStream_t);
-template qarvd_status launch_staged<128, 128, 2, 2, true>(const GemmArgs &, qarvd_dtype, hipStream_t);
-template qarvd_status launch_staged<256, 128, 2, 2, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
-template qarvd_status launch_staged<128, 128, 2, 2, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
+template qarvd_status launch_staged<256, 128, 2, 2, true, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
+template qarvd_status launch_staged<128, 128, 2, 2, true, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
+template qarvd_status launch_staged<256, 128, 2, 2, false, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
+template qarvd_status launch_staged<128, 128, 2, 2, false, false>(const GemmArgs &, qarvd_dtype, hipStream_t);
+template qarvd_status launch_staged<128, 128, 2, 2, true, true>(const GemmArgs &, qarvd_dtype, hipStream_t);
+template qarvd_status launch_staged<128, 128, 2, 2, false, true>(const GemmArgs &, qarvd_dtype, hipStream_t);
 
 }  // namespace qarvd_gemm

@@ -38,7 +38,7 @@ def random_codes_case(seed, M, N, K, K_o):
 
 
 @pytest.mark.parametrize("act", [q.ACT_NONE, q.ACT_GELU_TANH])
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("M,N,K,K_o", [(300, 208, 384, 32), (520, 384, 1536, 64), (257, 144, 640, 0),
                                        (64, 96, 130, 7), (33, 48, 96, 96), (700, 528, 512, 128), (1, 16, 32, 0)])
 def test_q8_gemm_codes_match_oracle(act, variant, M, N, K, K_o):

@@ -76,10 +76,16 @@ def test_quantize_weight_w4_forced_masks_and_errors():
         gpu_quantize_weight(L["W"], bits=4, ldwq=16)          # row stride too small
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 @pytest.mark.parametrize("M,N,K,K_o", [(300, 200, 384, 32), (520, 384, 1536, 64), (257, 136, 640, 0),
-                                       (64, 96, 130, 7), (33, 40, 96, 96), (700, 520, 512, 128)])
+                                       (64, 96, 130, 7), (33, 40, 96, 96), (700, 520, 512, 128),
+                                       # outside the fast path (the register-staged kernel): N % 8 != 0, an outlier
+                                       # block wider than 128 bytes, both, and an all-outlier layer
+                                       (300, 203, 384, 32), (130, 44, 256, 0), (257, 136, 640, 160),
+                                       (200, 77, 1536, 352), (65, 50, 300, 300)])
 def test_w4a8_gemm_accumulators_and_outputs(variant, M, N, K, K_o):
+    if variant in (1, 2) and (N % 8 or (K_o + 31) // 32 * 32 > 128):
+        pytest.skip("the LDS-direct tiles do not take this shape (refusal: test_w4a8_fast_variants_refuse_...)")
     rng = np.random.default_rng(variant * 31 + M + N + K + K_o)
     Xq = rng.integers(-127, 128, (M, K)).astype(np.int8)
     Wq = rng.integers(-7, 8, (N, K)).astype(np.int8)
@@ -118,13 +124,18 @@ def test_w4a8_extreme_accumulators():
     assert check_y(Y, ref) == 0
 
 
-def test_w4a8_unsupported_shapes_are_refused():
-    M, N, K, K_o = 32, 44, 256, 0                      # N % 8 != 0: no fast path for INT4 weights
+def test_w4a8_fast_variants_refuse_shapes_only_the_staged_kernel_takes():
+    M, N, K, K_o = 32, 44, 256, 0                      # N % 8 != 0: no LDS-direct path for INT4 weights
     w = q.DualScaleWeight(torch.zeros((N, 128), dtype=torch.uint8, device="cuda"), torch.ones(N, device="cuda"),
                           torch.ones(N, device="cuda"), None, K_o, N, K, None, 4)
-    with pytest.raises(q.QarvdError) as e:
-        q.w8a8_dual_gemm(torch.zeros((M, 256), dtype=torch.int8, device="cuda"), torch.ones(M, device="cuda"), w, None, M)
-    assert e.value.status == -2
+    Xq = torch.zeros((M, 256), dtype=torch.int8, device="cuda")
+    for variant in (1, 2):
+        with pytest.raises(q.QarvdError) as e:
+            q.w8a8_dual_gemm(Xq, torch.ones(M, device="cuda"), w, None, M, variant=variant)
+        assert e.value.status == -2
+    Y = q.w8a8_dual_gemm(Xq, torch.ones(M, device="cuda"), w, None, M, torch.float32)      # heuristic: staged
+    torch.cuda.synchronize()
+    assert not Y.any()
 
 
 @pytest.mark.parametrize("layer,rows", [("cfg1.linear", None), (wl.TARGET_LAYER, 40), ("cfg2.ffn_down.c64", 40),
