@@ -245,11 +245,15 @@ int32_t qarvd_w4_gemm_num_variants(void);
  * (quantization) applied to this layer's output with the next layer's scale):
  *     y      = the fp32 result of qarvd_w8a8_dual_gemm (same epilogue arithmetic, bias included)
  *     a      = y                          act = QARVD_ACT_NONE
- *            = gelu_tanh(y) in fp32       act = QARVD_ACT_GELU_TANH:  y * sigma(2 sqrt(2/pi) (y + 0.044715 y^3)),
- *              sigma(z) = 1 / (1 + 2^t), t = clamp(-z log2(e), -125, 125), 2^t = 2^rint(t) times the
- *              degree-7 Taylor polynomial of exp((t - rint(t)) ln 2); every operation a single fp32
- *              operation (fma where written as one), IEEE division
+ *            = gelu_tanh(y)               act = QARVD_ACT_GELU_TANH:
+ *              0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3)))
  *     Y8[m,n] = clip(rint(a / out_scale), -127, 127), round-half-even
+ * Without an activation the quotient is the IEEE fp32 quotient and Y8 is exactly that code.  With GELU
+ * the quotient is evaluated in fp32 as y / (s + s 2^t), t = -2 log2(e) sqrt(2/pi) (y + 0.044715 y^3)
+ * (one hardware 2^t and one hardware reciprocal per value), which lies within
+ * (4e-7 + 2e-6 |gelu(y)|) / out_scale of the real-valued quotient: Y8 is the code of the exact
+ * activation except where that quotient is this close to a rounding boundary k + 1/2, where it may be
+ * the neighbouring code.  Results are deterministic (the same inputs give the same bytes).
  * Column n of Y8 is output row n of Wq: to feed the next layer without a separate pass, give THIS
  * layer's weight rows (and bias) in the next layer's packed channel order, zero rows at its pad
  * positions, so that N = qarvd_packed_k(K_next, K_o_next) and Y8 is that layer's Xq with

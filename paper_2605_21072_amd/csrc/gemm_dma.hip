@@ -418,7 +418,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
     const int n_left = g.N - n0 - wn * G::WTN - (lane & 3) * EPC;     // columns from this lane's chunk to the matrix edge
     const bool has_o = DUAL && o_steps > 0;
     const bool wt = g.store_wt != 0;
-    const float out_rscale = sizeof(OutT) == 1 ? 1.0f / g.out_scale : 0.0f;     // IEEE division: RN(1 / s)
+    const StaticQuant sq = make_static_quant(sizeof(OutT) == 1 ? g.out_scale : 1.0f);
 
     // The epilogue is a chain of LDS round trips (scales in, patch out and back) around little arithmetic,
     // so it is written as a software pipeline over its units of work, in program order:
@@ -553,7 +553,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
                     // chained layer: activation, then the next layer's static scale (Eq. (quantization)); two
                     // blocks of 32 INT8 columns share a 64-byte patch row
                     static_assert(sizeof(OutT) != 1 || TN % 2 == 0, "INT8 output pairs the column blocks");
-                    const unsigned pk = quantize4_static(y, g.act == 1, g.out_scale, out_rscale);
+                    const unsigned pk = quantize4_static<out_is_gelu<OutT>::value>(y, sq);
                     const int c = 2 * (j & 1) + (q >> 1);
                     *reinterpret_cast<unsigned *>(patch + frow * PATCH_RS + ((c ^ pswz) << 4) + 8 * (q & 1) + 4 * fhalf) = pk;
                 } else if constexpr (sizeof(OutT) == 2) {
@@ -644,7 +644,8 @@ qarvd_status launch_dma_q8(const GemmArgs &g0, hipStream_t st)
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     g.store_wt = store_write_through(g, 1);
-    return launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, int8_t, false>(g, st);
+    return g.act == 1 ? launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, Int8GeluOut, false>(g, st)
+                      : launch_one<BM, BN, WM, WN, NSTAGE, DUAL, false, Int8Out, false>(g, st);
 }
 
 #define QARVD_INST_Q8(BM, BN, WM, WN, NS)                                                     \

@@ -354,7 +354,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
     const int n_left = g.N - n0 - wn * G::WTN - (lane & 3) * EPC;     // columns from this lane's chunk to the matrix edge
     const bool has_o = DUAL && o_steps > 0;
     const bool wt = g.store_wt != 0;
-    const float out_rscale = sizeof(OutT) == 1 ? 1.0f / g.out_scale : 0.0f;     // IEEE division: RN(1 / s)
+    const StaticQuant sq = make_static_quant(sizeof(OutT) == 1 ? g.out_scale : 1.0f);
 
     // Software pipeline over 32 x 32 blocks, as in the 64-byte-stage kernel: a patch is read back as soon as it
     // is complete and stored after the next block's arithmetic; the outlier MFMAs of the next block start before
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
                 bs[q] = *reinterpret_cast<const v4f *>(bs_lds + nt);
             }
         };
-        constexpr bool AO_AHEAD = HASO && sizeof(OutT) == 2 && !DBG && TM * TN < 8;   // 16 registers: only where they are to spare
+        constexpr bool AO_AHEAD = HASO && sizeof(OutT) <= 2 && !DBG && TM * TN < 8;   // 16 registers: only where they are to spare
         v16i ao_next;
         if constexpr (AO_AHEAD) ao_next = head_mma(blk_i(0), blk_j(0));
 #pragma unroll
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
                     // chained layer: activation, then the next layer's static scale (Eq. (quantization)); two
                     // blocks of 32 INT8 columns share a 64-byte patch row
                     static_assert(sizeof(OutT) != 1 || TN % 2 == 0, "INT8 output pairs the column blocks");
-                    const unsigned pk = quantize4_static(y, g.act == 1, g.out_scale, out_rscale);
+                    const unsigned pk = quantize4_static<out_is_gelu<OutT>::value>(y, sq);
                     const int c = 2 * (j & 1) + (q >> 1);
                     *reinterpret_cast<unsigned *>(patch + frow * PATCH2_RS + ((c ^ pswz) << 4) + 8 * (q & 1) + 4 * fhalf) = pk;
                 } else if constexpr (sizeof(OutT) == 2) {
@@ -571,7 +571,8 @@ qarvd_status launch_dma128_q8(const GemmArgs &g0, hipStream_t st)
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     g.store_wt = store_write_through(g, 1);
-    return launch128_one<BM, BN, WM, WN, NSTAGE, DUAL, false, int8_t>(g, st);
+    return g.act == 1 ? launch128_one<BM, BN, WM, WN, NSTAGE, DUAL, false, Int8GeluOut>(g, st)
+                      : launch128_one<BM, BN, WM, WN, NSTAGE, DUAL, false, Int8Out>(g, st);
 }
 
 #define QARVD_INST128_Q8(BM, BN, WM, WN, NS)                                                         \

@@ -89,76 +89,68 @@ __device__ __forceinline__ void buffer_store16(void *base, int bytes, int voffse
 }
 
 // ---- chained-layer epilogue: activation, then the next layer's static-scale INT8 code ---------------------
-// GELU, tanh form, in fp32 with every operation spelled out (the sequence the CPU reference of the
-// chained-layer epilogue defines, so both sides get the same bits and hence the same INT8 codes):
-//   gelu(x) = x * sigma(2u),  u = sqrt(2/pi) (x + 0.044715 x^3),  sigma(z) = 1 / (1 + exp(-z)),
-//   exp(-z) = 2^t,  t = x (C0 + C1 x^2) clamped to [-125, 125]  (C0 = -2 log2(e) sqrt(2/pi), C1 = 0.044715 C0),
-//   n = rint(t), 2^(t-n) by the degree-7 Taylor polynomial of exp((t-n) ln 2), n added into the exponent
-//   field; IEEE division.
-__device__ __forceinline__ float gelu_exponent(float x)       // t above: shared by the exact and the fast path
-{
-    const float x2 = x * x;
-    const float inner = fmaf(-0.102943240f, x2, -2.30220820f);
-    const float t = x * inner;
-    return fminf(fmaxf(t, -125.0f), 125.0f);
-}
+// Output types of the chained kernels: one byte per element either way; the type only selects the activation
+// at compile time (the epilogue is straight-line code, unrolled over the whole wave tile, and a run-time
+// choice doubled it past what the instruction cache holds).
+struct Int8Out { int8_t v; };          // no activation
+struct Int8GeluOut { int8_t v; };      // GELU (tanh form) before the quantization
+template <typename T> struct out_is_gelu { static constexpr bool value = false; };
+template <> struct out_is_gelu<Int8GeluOut> { static constexpr bool value = true; };
 
-__device__ __forceinline__ float gelu_tanh_exact(float x, float t)
+// Per-wave constants of the static-scale quantizer below.
+struct StaticQuant {
+    float s, rs, bound;      // the scale, RN(1 / s) by IEEE division, RN(127 s)
+};
+__device__ __forceinline__ StaticQuant make_static_quant(float s)
 {
-    const float n = rintf(t);
-    const float f = t - n;
-    const float g = f * 0.693147182f;
-    float p = 1.0f / 5040.0f;
-    p = fmaf(p, g, 1.0f / 720.0f);
-    p = fmaf(p, g, 1.0f / 120.0f);
-    p = fmaf(p, g, 1.0f / 24.0f);
-    p = fmaf(p, g, 1.0f / 6.0f);
-    p = fmaf(p, g, 0.5f);
-    p = fmaf(p, g, 1.0f);
-    p = fmaf(p, g, 1.0f);
-    const float e = __int_as_float(__float_as_int(p) + (int)n * (1 << 23));
-    const float sg = 1.0f / (1.0f + e);
-    return x * sg;
+    return StaticQuant{s, 1.0f / s, 127.0f * s};
 }
 
 // Four fp32 results -> four INT8 codes in one dword (byte e = code of y[e]):
-//     code = clip(rint(a / s), -127, 127),  a = y or gelu(y) as defined above,  rs = RN(1 / s).
-// Common path, a handful of instructions per value: a~ from the hardware 2^t and reciprocal (each within
-// 1 ulp; t itself is the exact sequence's), q~ = a~ * rs, rounded by adding 1.5 * 2^23 (round-half-even, and
-// the code lands in the low byte of the sum).  How far q~ can be from the exact sequence's RN(a / s), while
-// |a / s| <= 127.5:   2^t and the polynomial differ by < 3.5e-7 relative, 1 + e, the reciprocal against the
-// division and the products add < 3.5e-7, rs and the last product < 1.8e-7: under 9e-7 relative, 1.2e-4 in
-// units of a code.  Beyond 127.5 both sides clip.  A value whose q~ is more than 5e-4 away from every
-// half-integer therefore rounds to the same code; the others (about 1 in 1000) take the exact sequence.
-__device__ __forceinline__ unsigned quantize4_static(const float (&y)[4], bool gelu, float s, float rs)
+//     code = clip(rint(a / s), -127, 127),  a = y (the IEEE fp32 quotient, exactly) or gelu(y) (see below).
+// The epilogue is bound by vector-ALU issue (a wave64 instruction occupies its SIMD for four cycles and the
+// code is unrolled over 128 values per lane), so the quotient is not taken with the ~13-instruction division
+// sequence but as a product with RN(1 / s) corrected twice with fused multiply-adds,
+//     q0 = a rs;  q1 = q0 + (a - q0 s) rs;  q2 = q1 + (a - q1 s) rs,
+// which IS the correctly rounded quotient RN(a / s): rs has a relative error below 2^-24, so q0 is within
+// 1.5 ulp of a / s; the first step leaves q1 a faithful rounding (the residual, rounded or not, puts
+// q0 + r rs within 2^-21 ulp of a / s before the rounding), and for a faithful q1 the residual a - q1 s is
+// exact and the second step rounds correctly (Markstein's theorem on FMA division).  No intermediate can
+// overflow because a is first clamped to +-RN(127 s): beyond that bound the code is +-127 on both sides, and
+// at the bound the quotient is within 2^-23 of 127, so no clip of the result is needed either.  Residuals
+// stay exact down to s = 1e-30 (their last bit is above 2^-149).  Adding 1.5 * 2^23 rounds half-to-even and
+// leaves the two's-complement code in the low byte of the sum.
+//
+// With GELU (tanh form) the activation and the quotient share one reciprocal:
+//   gelu(x) = x * sigma(2u),  u = sqrt(2/pi) (x + 0.044715 x^3),  sigma(z) = 1 / (1 + exp(-z)),
+//   exp(-z) = 2^t,  t = x (C0 + C1 x^2)  (C0 = -2 log2(e) sqrt(2/pi), C1 = 0.044715 C0),
+//   gelu(x) / s = x / (s + s 2^t)
+// with the hardware 2^t and reciprocal (1 ulp each; 2^t overflows to inf and underflows to 0 where sigma is 0
+// and 1 to working precision).  Against the real-valued gelu(x) / s: t carries at most four roundings
+// (2.4e-7 |t|), which 2^t turns into a relative error of 1.7e-7 |t| on exp(-z); sigma damps that by
+// exp(-z) / (1 + exp(-z)), and where |t| is large either that factor or the result itself is tiny; 2^t, the
+// fma, the reciprocal and the product add under 4e-7.  The quotient is within (4e-7 + 2e-6 |gelu(x)|) / s of
+// the definition's, so the code can differ from the one rounded from the exact activation, by one, only
+// where that quotient is this close to a rounding boundary (the rule the parity tests apply).
+template <bool GELU>
+__device__ __forceinline__ unsigned quantize4_static(const float (&y)[4], const StaticQuant &sq)
 {
     constexpr float MAGIC = 12582912.0f;      // 1.5 * 2^23
     float m[4];
-    unsigned redo = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        float a = y[e];
-        if (gelu) {
-            const float t = gelu_exponent(y[e]);
-            a = y[e] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
-        }
-        const float qa = fminf(fmaxf(a * rs, -127.0f), 127.0f);
-        m[e] = qa + MAGIC;
-        const float r = m[e] - MAGIC;
-        redo |= (fabsf(qa - r) < 0.4995f) ? 0u : (1u << e);      // NaN lands here too
-    }
-    if (redo) {
-#pragma unroll 1
-        for (int e = 0; e < 4; ++e) {
-            if ((redo >> e) & 1u) {
-                const float x = e == 0 ? y[0] : e == 1 ? y[1] : e == 2 ? y[2] : y[3];
-                const float a = gelu ? gelu_tanh_exact(x, gelu_exponent(x)) : x;
-                const float me = (float)quantize_i8(a, s) + MAGIC;
-                m[0] = e == 0 ? me : m[0];
-                m[1] = e == 1 ? me : m[1];
-                m[2] = e == 2 ? me : m[2];
-                m[3] = e == 3 ? me : m[3];
-            }
+        if constexpr (GELU) {
+            const float x = y[e];
+            const float inner = fmaf(-0.102943240f, x * x, -2.30220820f);
+            const float d = fmaf(sq.s, __builtin_amdgcn_exp2f(x * inner), sq.s);
+            const float q = x * __builtin_amdgcn_rcpf(d);
+            m[e] = __builtin_amdgcn_fmed3f(q, -127.0f, 127.0f) + MAGIC;
+        } else {
+            const float a = __builtin_amdgcn_fmed3f(y[e], -sq.bound, sq.bound);
+            const float q0 = a * sq.rs;
+            const float q1 = fmaf(fmaf(-q0, sq.s, a), sq.rs, q0);
+            const float q2 = fmaf(fmaf(-q1, sq.s, a), sq.rs, q1);
+            m[e] = q2 + MAGIC;
         }
     }
     // byte 0 of each sum, gathered: v_perm_b32 picks bytes 0..3 from its second operand, 4..7 from its first

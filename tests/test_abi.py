@@ -142,8 +142,8 @@ def test_bad_arguments_of_the_widened_entry_points(lib):
     a[17] = 9
     assert w4(*a) == INVALID
     a = list(ok4)
-    a[9], a[14] = 12, 12
-    assert w4(*a) == UNSUPPORTED                              # N % 8 != 0: no fast path, and INT4 has no other
+    a[9], a[14], a[17] = 12, 12, 1
+    assert w4(*a) == UNSUPPORTED                              # N % 8 != 0: not for the LDS-direct tile asked for
     # percentile-clip search: flag values and its K limit
     ko = C.c_int32(0)
     cfg = _DetectCfg()

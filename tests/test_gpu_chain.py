@@ -74,12 +74,18 @@ def test_q8_gemm_without_bias():
         q.w8a8_dual_gemm_q8(Xd, dev(sx), w, None, M, 0.0, 1)
 
 
-@pytest.mark.parametrize("act", [0, 1])
-def test_q8_rounding_boundaries_and_dense_sweep(act):
-    """The kernel rounds most values on a short path and re-does the few that sit near a rounding boundary
-    with the exact sequence: drive it with values ON and next to every boundary (k + 1/2) * s (identity), and
-    with a dense sweep of the activation's input range (GELU).  Zero activations make y equal the bias."""
-    s_out = float(np.float32(0.0371))
+ALL_ONES = float(np.array([0x3F7FFFFF], np.uint32).view(np.float32)[0])        # 1 - 2^-24: every mantissa bit set
+
+
+@pytest.mark.parametrize("act,s_out", [(0, 0.0371), (0, 1.0), (0, ALL_ONES), (0, 3.3e-5), (0, 517.3), (0, 2.5e-30),
+                                       (0, 7.0e29 / 130), (1, 0.0371), (1, 0.004)])
+def test_q8_rounding_boundaries_and_dense_sweep(act, s_out):
+    """Without an activation the kernel forms the quotient as a product with 1 / s corrected by two fused
+    multiply-adds, which must equal the IEEE quotient: drive it with values ON and up to four ulps either side
+    of every rounding boundary (k + 1/2) * s, for ordinary scales, a power of two, a mantissa of all ones and
+    the ends of the accepted range.  With GELU: a dense sweep of the activation's input range.  Zero
+    activations make y equal the bias."""
+    s_out = float(np.float32(s_out))
     if act == 0:
         k = np.arange(-130, 130, dtype=np.float64) + 0.5
         centre = (k * np.float64(np.float32(s_out))).astype(np.float32)
@@ -89,7 +95,7 @@ def test_q8_rounding_boundaries_and_dense_sweep(act):
             for _ in range(steps):
                 up, dn = np.nextafter(up, np.float32(np.inf)), np.nextafter(dn, np.float32(-np.inf))
             vals += [up, dn]
-        b = np.concatenate(vals + [np.float32([0.0, -0.0, 1e-38, -1e-38, 1e30, -1e30, 4.7, -4.7])])
+        b = np.concatenate(vals + [np.float32([0.0, -0.0, 1e-38, -1e-38, 1e30, -1e30, 4.7, -4.7, 3e38, -3e38])])
         b = np.concatenate([b, np.zeros(-len(b) % 16, np.float32)]).astype(np.float32)
     else:
         b = np.concatenate([np.linspace(-9, 9, 49152), np.linspace(-0.9, 0.9, 16384)]).astype(np.float32)
