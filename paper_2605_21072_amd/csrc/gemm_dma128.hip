@@ -30,11 +30,14 @@ constexpr int KS2 = BK2 / 32;             // MFMA k-steps per stage
 constexpr int PATCH2_RS = 64;
 constexpr int PATCH2_BYTES = 32 * PATCH2_RS;
 
-// Swizzle for 128-byte LDS rows (eight 16-byte slots): a ds_read_b128 is served in four passes of lanes
-// {8p..8p+7, 32+8p..32+8p+7}, i.e. eight consecutive rows times the two halves of a k-step.  Rows of equal
-// parity share their banks (a row covers half of the 64 banks), so rows r, r+2, r+4, r+6 take their chunk
-// pair {2s, 2s+1} at four different slot pairs.
-__device__ __forceinline__ int swz128(int r) { return ((r >> 1) & 3) << 1; }
+// Swizzle for 128-byte LDS rows (eight 16-byte slots).  A row covers half of the 64 banks, so rows of equal
+// parity share their banks.  A fragment read (ds_read_b128, lane l -> row l & 31, half l >> 5 of a k-step)
+// must spread over all banks both when the hardware groups lanes {8p..8p+7, 32+8p..32+8p+7} (eight consecutive
+// rows times the two halves of a k-step) and when it groups sixteen consecutive lanes (sixteen consecutive
+// rows, one half): rows r, r+2, r+4, r+6 take their chunk pair {2s, 2s+1} at four different slot pairs, and
+// rows r and r+8 swap the two slots of a pair.  (With the first rule alone the bank-conflict counter of the
+// target-shape kernel read ten times what the 64-byte-stage kernel's does.)
+__device__ __forceinline__ int swz128(int r) { return (((r >> 1) & 3) << 1) | ((r >> 3) & 1); }
 
 template <int BM, int BN, int WM, int WN, int NSTAGE>
 struct Geo2 {
@@ -54,6 +57,7 @@ struct Geo2 {
     static constexpr int LDS_BYTES = SCALES_OFF + SCALE_BYTES;
     static constexpr int SPT = (NSCALE + THREADS - 1) / THREADS;
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "row groups of eight must divide over the waves");
+    static_assert(NW % 2 == 0, "the load swizzle takes bit 3 of a row from the wave number");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is TM x TN blocks of 32 x 32");
     static_assert(TM * TN * 16 <= 128, "two waves per SIMD: at most 128 accumulator registers");
     static_assert(PATCHES <= STG, "the output patches fit into one stage");
@@ -80,11 +84,11 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
     int m0, n0;                                    // tile being computed
 
     // ---- LDS-direct load addressing: load i of this wave fills rows (NW*i + wave)*8 .. +8 of the operand tile;
-    // lane l fills slot (l & 7) of row (l >> 3) with global chunk (l & 7) ^ swz128(row).  Tile base in SGPRs, one
+    // lane l fills slot (l & 7) of row (l >> 3) of those with global chunk (l & 7) ^ swz128(row in the tile).  Tile base in SGPRs, one
     // byte offset per lane and load, the K position as scalar offset.  Rows past the matrix are clamped to its
     // last row (their products land in rows / columns that are never stored).
     const int drow = lane >> 3;
-    const int dchunk = ((lane & 7) ^ swz128(drow)) << 4;
+    const int dchunk = ((lane & 7) ^ swz128(8 * (wave & 1) + drow)) << 4;      // (NW is even: row bit 3 = wave bit 0)
     const int8_t *base_a, *base_b;
     int va[NA], vb[NB];
     int lm0, ln0;                                  // tile the load addressing points at
