@@ -456,13 +456,16 @@ def side_measurements(out, args, layers, tgt, q, wl, torch, np, dev, run_quant, 
             lt = layers[tgt[len(tgt) // 2]]
             w4 = q.quantize_weight(torch.from_numpy(wl.make_layer(lt["spec"])["W"]).to(dev), want_norms=False, bits=4)
             Xq4, sx4 = q.quant_act(lt["X"], w4.perm if w4.K_o else None, w4.K_o)
-            us4 = time_us(lambda: q.w8a8_dual_gemm(Xq4, sx4, w4, lt["bias"], lt["spec"].M, Y=lt["Y"]))
             us8 = time_us(lambda: run_gemm(lt))
+            us4 = time_us(lambda: q.w8a8_dual_gemm(Xq4, sx4, w4, lt["bias"], lt["spec"].M, Y=lt["Y"]))
+            us8 = min(us8, time_us(lambda: run_gemm(lt)))          # alternated, the better of two: the clock the chip
+            us4 = min(us4, time_us(lambda: q.w8a8_dual_gemm(Xq4, sx4, w4, lt["bias"], lt["spec"].M, Y=lt["Y"])))   # holds drifts
             out["w4a8_target_layer"] = dict(layer=lt["spec"].name, gemm_us=round(us4, 2), w8a8_gemm_us=round(us8, 2),
                                             gemm_tops=round(2.0 * lt["spec"].macs / us4 / 1e6, 1),
                                             weight_bytes=int(w4.N * w4.kp // 2), int8_weight_bytes=int(w4.N * w4.kp),
                                             note="back-to-back launches of qarvd_w4a8_dual_gemm and of qarvd_w8a8_dual_gemm on "
-                                                 "the target shape (compute-bound: halving the weight bytes cannot pay here)")
+                                                 "the target shape (compute-bound: halving the weight bytes cannot pay here, "
+                                                 "and the INT4 path runs on the 64-byte-stage tiles only)")
             del w4, Xq4, sx4
         except Exception as e:  # diagnostic only
             out["w4a8_target_layer"] = dict(error=str(e))
@@ -569,6 +572,20 @@ def side_measurements(out, args, layers, tgt, q, wl, torch, np, dev, run_quant, 
             del wf, Xqf, Yf3
         except Exception as e:  # diagnostic only
             out["fused_qkv"] = dict(error=str(e))
+    try:        # context: the vendor library's plain INT8 GEMM (INT32 out, no scales, no epilogue) on the same shapes
+        rows = []
+        for (M, K, N) in ((4680, 1536, 8960), (4680, 8960, 1536), (4680, 1536, 1536)):
+            A = torch.randint(-127, 128, (M, K), dtype=torch.int8, device=dev)
+            Bt = torch.randint(-127, 128, (N, K), dtype=torch.int8, device=dev).t()      # K x N, column-major
+            us = time_us(lambda: torch._int_mm(A, Bt), 20)
+            rows.append(dict(M=M, K=K, N=N, us=round(us, 1), tops=round(2.0 * M * N * K / us / 1e6, 1)))
+            del A, Bt
+        out["vendor_int8_gemm"] = dict(rows=rows, note="torch._int_mm (hipBLASLt INT8, INT32 output) launched back to back: "
+                                                      "what the vendor's own kernels sustain on these shapes, for scale "
+                                                      "beside gemm_back_to_back_us; not the same operation (no dual scale, "
+                                                      "no de-quantization, four times the output bytes)")
+    except Exception as e:  # diagnostic only
+        out["vendor_int8_gemm"] = dict(error=str(e)[:200])
 
 
 if __name__ == "__main__":
