@@ -44,7 +44,34 @@ struct ActArgs {
     float *s_x;
     float static_scale;
     int32_t M, K, K_o, n_off, kp;
+    int32_t store_wt;      // 1: Xq leaves through write-through stores (see store_q)
 };
+
+// Stores of the quantized rows.  A kernel ends with a write-back of what its XCDs' L2s still hold, and the
+// consumer (the GEMM, on any XCD) reads Xq from memory either way; for an Xq of a few MB that write-back is
+// 1-2 us at the end of a 9 us kernel.  Write-through stores (sc0 sc1) send the bytes on while the kernel still
+// computes.  Used when the whole Xq is at most 40 MB (beyond that the extra traffic during the kernel costs
+// more than the tail); `off` is the byte offset from a.Xq (the host checked that it fits 31 bits).
+template <typename V>
+__device__ __forceinline__ void store_q(const ActArgs &a, size_t off, V v)
+{
+    static_assert(sizeof(V) == 16 || sizeof(V) == 4, "16-byte image chunks or 4-byte words");
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (a.store_wt) {
+        const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(a.Xq, 0, 0x7fffffff, 0x00020000);
+        if constexpr (sizeof(V) == 16) {
+            typedef unsigned int v4u_t __attribute__((ext_vector_type(4)));
+            const v4u_t d = __builtin_bit_cast(v4u_t, v);
+            __builtin_amdgcn_raw_buffer_store_b128(d, r, (int)off, 0, 17);
+            asm volatile("s_nop 1" : : "v"(d));      // a 16-byte store reads its data registers a cycle late
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, v), r, (int)off, 0, 17);
+        }
+        return;
+    }
+#endif
+    *reinterpret_cast<V *>(a.Xq + off) = v;
+}
 
 // Workgroup-wide max of a non-negative value; `red` holds one float per wave.
 template <int NWAVE = 4>
@@ -154,7 +181,7 @@ __global__ __launch_bounds__(NT) void quant_act_rows_kernel(ActArgs a)
         }
         const bool zero = s == 0.0f;                       // all-zero token (or zero static scale): q = 0
         const float r = __builtin_amdgcn_rcpf(s);
-        int8_t *out = a.Xq + (size_t)m * a.ldxq;
+        const size_t out = (size_t)m * a.ldxq;             // byte offset of the row in Xq
         if constexpr (IDENT) {
 #pragma unroll
             for (int c = 0; c < CH; ++c) {
@@ -165,7 +192,7 @@ __global__ __launch_bounds__(NT) void quant_act_rows_kernel(ActArgs a)
                         w = (uint32_t)(quantize_i8_fast(v[c].x, s, r) & 255) | ((uint32_t)(quantize_i8_fast(v[c].y, s, r) & 255) << 8) |
                             ((uint32_t)(quantize_i8_fast(v[c].z, s, r) & 255) << 16) | ((uint32_t)(quantize_i8_fast(v[c].w, s, r) & 255) << 24);
                     }
-                    *reinterpret_cast<uint32_t *>(out + k) = w;
+                    store_q(a, out + k, w);
                 }
             }
         } else {
@@ -181,8 +208,7 @@ __global__ __launch_bounds__(NT) void quant_act_rows_kernel(ActArgs a)
                 }
             }
             __syncthreads();
-            for (int i = tid; i < kp / 16; i += NT)
-                reinterpret_cast<uint4 *>(out)[i] = reinterpret_cast<const uint4 *>(q)[i];
+            for (int i = tid; i < kp / 16; i += NT) store_q(a, out + 16 * (size_t)i, reinterpret_cast<const uint4 *>(q)[i]);
         }
         if (more) {
 #pragma unroll
@@ -283,9 +309,8 @@ __global__ __launch_bounds__(TPB) void quant_act_wave_kernel(ActArgs a)
         }
         if (m + n_waves < a.M) load_row(m + n_waves);     // next row in flight during the copy-out
         // the image is private to this wave and LDS operations of one wave complete in order
-        int8_t *out = a.Xq + (size_t)m * a.ldxq;
-        for (int i = lane; i < kp / 16; i += 64)
-            reinterpret_cast<uint4 *>(out)[i] = reinterpret_cast<const uint4 *>(img)[i];
+        const size_t out = (size_t)m * a.ldxq;
+        for (int i = lane; i < kp / 16; i += 64) store_q(a, out + 16 * (size_t)i, reinterpret_cast<const uint4 *>(img)[i]);
     }
 }
 
@@ -411,6 +436,7 @@ qarvd_status quant_act_common(const void *X, qarvd_dtype xdt, int32_t M, int32_t
     ActArgs a;
     a.X = X; a.ldx = ldx; a.perm = perm; a.Xq = Xq; a.ldxq = ldxq; a.s_x = s_x; a.static_scale = scale;
     a.M = M; a.K = K; a.K_o = K_o; a.n_off = g.n_off; a.kp = g.kp;
+    a.store_wt = ((size_t)M * (size_t)g.kp <= ((size_t)40 << 20) && (size_t)M * (size_t)ldxq < ((size_t)1 << 31)) ? 1 : 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (xdt == QARVD_F32)
         return is_static ? dispatch<float, true>(a, st) : dispatch<float, false>(a, st);
