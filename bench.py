@@ -448,6 +448,17 @@ def compact_config(cfg, args, wl, torch, np, build_layers, timed_steps, instrume
     if note:
         res["note"] = note
         res["ms_per_step_full_stack"] = round(10.0 * ms, 3)
+        # the paper's block has ten linears including the cross-attention output projection, the workload list of
+        # the metric names nine: the stack without it, from the per-layer in-step times of the same pass
+        cross_o = [i for i, l in enumerate(layers) if "cross_o" in l["spec"].name]
+        if cross_o:
+            t_all = float(linear_us.sum())
+            t_wo = t_all - float(linear_us[cross_o].sum())
+            ops_wo = ops - sum(2.0 * layers[i]["spec"].macs for i in cross_o)
+            res["without_cross_attn_o"] = dict(layers=len(layers) - len(cross_o),
+                                               ms_per_step_full_stack=round(10.0 * ms * t_wo / t_all, 3),
+                                               value=round(ops_wo / (ms * 1e-3 * t_wo / t_all) / 1e12, 2),
+                                               note="scaled from the step above by the share of the event-timed linears that remain")
     del layers
     return res
 
