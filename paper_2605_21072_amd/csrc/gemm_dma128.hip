@@ -307,10 +307,39 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
         __builtin_amdgcn_sched_barrier(0);
         stage = nstage;
     }
-    // drain: the last NSTAGE tiles, nothing left to issue; the head tile is the last of them and only its
+    // Two stages: the second-to-last K tile is always a normal one; it runs through a copy of the scheduled
+    // iteration that has nothing to refill, which leaves only the last tile (the head tile, if any) to the
+    // unscheduled drain loop below.
+    int drain_from = T > NSTAGE ? T - NSTAGE : 0;
+    if (NSTAGE == 2 && i_lim == TM && T >= 2) {
+        const unsigned char *sb = smem + stage * STG;
+        const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
+        load_frags(sb, 1);
+        mma(0);
+        interleave_reads();
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(sb, 2);
+        mma(1);
+        interleave_reads();
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(sb, 3);
+        mma(2);
+        interleave_reads();
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vmcnt<0>();
+        wait_lgkmcnt0();
+        __builtin_amdgcn_s_barrier();
+        load_frags(smem + nstage * STG, 0);
+        mma(3);
+        interleave_reads();
+        __builtin_amdgcn_sched_barrier(0);
+        stage = nstage;
+        drain_from = T - 1;
+    }
+    // drain: the last tiles, nothing left to issue; the head tile is the last of them and only its
     // normal k-steps (those past the outlier range) are summed here
 #pragma unroll 1
-    for (int it = (T > NSTAGE ? T - NSTAGE : 0); it < T; ++it) {
+    for (int it = drain_from; it < T; ++it) {
         const unsigned char *sb = smem + stage * STG;
         const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
         const int first = it < Tn ? 0 : o_steps;    // first k-step of this tile that belongs to the normal range
