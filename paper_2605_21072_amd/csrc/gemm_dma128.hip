@@ -170,6 +170,22 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks & 1][j], xf[ks & 1][i], acc[i][j], 0, 0, 0);
     };
+    auto mma_z = [&](int ks) {      // the same from zero accumulators (first k-step of a tile)
+        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ks & 1][j], xf[ks & 1][i], zero, 0, 0, 0);
+    };
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    };
     // last row of tiles: 32-row blocks that lie entirely below the matrix are left out
     int i_lim = TM;
     auto mma_r = [&](int ks) {
@@ -230,13 +246,6 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
     n0 = ln0;
     const int next_tile = tile + (int)gridDim.x;
     const bool more = next_tile < ntiles;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-
     // The wait counts assume only stage loads are outstanding; the previous tile's output stores may still be,
     // but they are older than every load issued after them, so the waits only get stricter.  A tile whose first
     // stage was prefetched under the previous epilogue waits for nothing here: that epilogue waited for the
@@ -257,6 +266,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
     // Before the barrier a wave waits for its own loads of stage it+1 and for its own LDS reads (the last
     // fragments of this stage), so after the barrier stage it+1 is complete and stage `it` is dead.
     if (i_lim < TM) {                            // ragged tile: same steps, unneeded row blocks left out
+        clear_acc();
 #pragma unroll 1
         for (int it = 0; it < T - NSTAGE; ++it) {
             const unsigned char *sb = smem + stage * STG;
@@ -275,8 +285,39 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
             mma_r(3);
             stage = nstage;
         }
-    } else
-    for (int it = 0; it < T - NSTAGE; ++it) {    // steady state: every tile here is a normal tile
+    } else {
+    // The accumulators start from the MFMA's inline zero in a first iteration of its own (128 register moves less
+    // per tile and wave than clearing them, in a phase that is bound by vector-ALU issue).
+    int it0 = 0;
+    if (T > NSTAGE) {
+        const unsigned char *sb = smem + stage * STG;
+        const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
+        load_frags(sb, 1);
+        mma_z(0);
+        interleave_reads();
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(sb, 2);
+        mma(1);
+        interleave_reads();
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(sb, 3);
+        mma(2);
+        interleave_reads();
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vmcnt<(NSTAGE - 2) * NL>();
+        wait_lgkmcnt0();
+        __builtin_amdgcn_s_barrier();
+        load_frags(smem + nstage * STG, 0);
+        issue(seq(NSTAGE), stage);
+        mma(3);
+        interleave_reads_and_loads();
+        __builtin_amdgcn_sched_barrier(0);
+        stage = nstage;
+        it0 = 1;
+    } else {
+        clear_acc();
+    }
+    for (int it = it0; it < T - NSTAGE; ++it) {    // steady state: every tile here is a normal tile
         const unsigned char *sb = smem + stage * STG;
         const int nstage = stage + 1 == NSTAGE ? 0 : stage + 1;
         load_frags(sb, 1);
@@ -306,6 +347,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
         interleave_reads_and_loads();
         __builtin_amdgcn_sched_barrier(0);
         stage = nstage;
+    }
     }
     // Two stages: the second-to-last K tile is always a normal one; it runs through a copy of the scheduled
     // iteration that has nothing to refill, which leaves only the last tile (the head tile, if any) to the
