@@ -450,7 +450,13 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
                 // the next tile's first stages were issued when this epilogue began; waiting for them before the
                 // first output store means no later stage wait has an output store ahead of it in the counter
                 __builtin_amdgcn_sched_barrier(0);
+#if QARVD_PROF == 2
+                const long long q0 = clock64();
+#endif
                 wait_vmcnt<0>();
+#if QARVD_PROF == 2
+                p_vm += clock64() - q0;      // (diagnostic build 2: o[1] = ticks spent in this wait, summed over the tiles)
+#endif
                 __builtin_amdgcn_sched_barrier(0);
                 stored = true;
             }
@@ -583,7 +589,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_dma128_kernel(GemmArgs g
 #if QARVD_PROF
     {
         const long long p_t2 = clock64();
-        if (p_tiles == 0) p_vm = p_t0 - p_mark; else p_pro += p_t0 - p_mark;
+        if (p_tiles == 0) { if (QARVD_PROF != 2) p_vm = p_t0 - p_mark; } else p_pro += p_t0 - p_mark;
         p_loop += p_t1 - p_t0; p_epi += p_t2 - p_t1; p_mark = p_t2; ++p_tiles;
     }
 #endif
