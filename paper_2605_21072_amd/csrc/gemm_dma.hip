@@ -436,7 +436,10 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
         constexpr bool HASO = decltype(haso_tag)::value;
         constexpr int NBLK = TM * TN;
         auto blk_i = [&](int b) { return b / TN; };
-        auto blk_j = [&](int b) { return b % TN; };
+        // column blocks run back and forth (0 .. TN-1, TN-1 .. 0, ...): consecutive row blocks then share a column
+        // block at the turn, and its scales and biases -- twelve broadcast 16-byte LDS reads per lane, the
+        // epilogue's largest LDS traffic -- are loaded once for both (5 loads instead of 8 per 4 x 2 wave tile)
+        auto blk_j = [&](int b) { return ((b / TN) & 1) ? TN - 1 - b % TN : b % TN; };
 
         v4i pend[2];
         int pend_voff = 0, pend_soff = 0;
@@ -505,7 +508,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
 #pragma unroll
         for (int b = 0; b < NBLK; ++b) {
             const int i = blk_i(b), j = blk_j(b);
-            load_cols(j);
+            if (b == 0 || blk_j(b - 1) != j) load_cols(j);
             v16i ao;
             if constexpr (AO_AHEAD) {
                 ao = ao_next;
@@ -569,7 +572,7 @@ __global__ __launch_bounds__(64 * WM * WN, (Geo<BM, BN, WM, WN, NSTAGE, W4>::WAV
             }
             if constexpr (sizeof(OutT) == 2) flush(i, j * 32);
             if constexpr (sizeof(OutT) == 1) {
-                if (j & 1) flush(i, (j - 1) * 32);
+                if (b & 1) flush(i, (j & ~1) * 32);        // both blocks of a 64-column pair are in the patch
             }
         }
         flush_commit();
